@@ -1,0 +1,184 @@
+"""ctypes binding of the C oracle (oracle/sta_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the
+benchmark's cpu_baseline leg.  It never imports the HIP package and the HIP
+package never imports it.  All windows here are in TOKENS, as the paper's
+mask algorithm takes them ("kernel size"); `window_tiles_to_tokens` converts
+from the tile units the GPU boundary uses.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsta_oracle.so")
+_lib = None
+
+_I3 = ctypes.c_int * 3
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build_oracle  # local build step: gcc only
+        build_oracle.build(force=True)
+    lib = ctypes.CDLL(_LIB_PATH)
+    c_long, c_int, c_double, c_void = ctypes.c_long, ctypes.c_int, ctypes.c_double, ctypes.c_void_p
+    lib.sta_oracle_keep.argtypes = [_I3, _I3, _I3, _I3, _I3]
+    lib.sta_oracle_keep.restype = c_int
+    lib.sta_oracle_attention.argtypes = [c_void, c_void, c_void, c_int, _I3, _I3, _I3, c_double,
+                                         c_void, c_long, c_void]
+    lib.sta_oracle_attention.restype = c_int
+    lib.sta_oracle_probs.argtypes = [c_void, c_void, c_int, _I3, _I3, _I3, c_double, c_long,
+                                     c_void, c_void]
+    lib.sta_oracle_probs.restype = c_int
+    lib.sta_oracle_tile_order.argtypes = [_I3, _I3, c_void]
+    lib.sta_oracle_tile_order.restype = c_int
+    for name in ("sta_oracle_tile_permute", "sta_oracle_untile"):
+        fn = getattr(lib, name)
+        fn.argtypes = [c_void, c_void, c_long, c_long, _I3, _I3]
+        fn.restype = c_int
+    lib.sta_oracle_key_tiles.argtypes = [_I3, _I3, _I3, c_void, c_void]
+    lib.sta_oracle_key_tiles.restype = c_int
+    lib.sta_oracle_block_census.argtypes = [_I3, _I3, _I3, c_void, c_void, c_void]
+    lib.sta_oracle_block_census.restype = c_int
+    lib.sta_oracle_num_threads.argtypes = []
+    lib.sta_oracle_num_threads.restype = c_int
+    _lib = lib
+    return lib
+
+
+def _i3(x):
+    x = [int(v) for v in x]
+    assert len(x) == 3
+    return _I3(*x)
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def window_tiles_to_tokens(window_tiles, tile):
+    """Window in tiles -> window in tokens (the algorithm's kernel size)."""
+    return [int(w) * int(t) for w, t in zip(window_tiles, tile)]
+
+
+def num_threads() -> int:
+    return int(_load().sta_oracle_num_threads())
+
+
+def keep(q, k, grid, window_tokens, tile) -> bool:
+    """Mask predicate for one (query token, key token) pair of coordinates."""
+    return bool(_load().sta_oracle_keep(_i3(q), _i3(k), _i3(grid), _i3(window_tokens), _i3(tile)))
+
+
+def attention(q, k, v, grid, tile, window_tokens, scale=None, query_idx=None):
+    """Masked attention (Eq. 1) of ONE head in raster order.
+
+    q, k, v: [N, d] arrays (any float type; values are taken exactly as fp32).
+    query_idx: raster indices to evaluate (default: all).  Returns [nq, d] fp64.
+    """
+    lib = _load()
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    N, d = q.shape
+    assert N == int(grid[0]) * int(grid[1]) * int(grid[2]) and k.shape == (N, d) and v.shape == (N, d)
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    if query_idx is None:
+        query_idx = np.arange(N, dtype=np.int64)
+    query_idx = np.ascontiguousarray(query_idx, dtype=np.int64)
+    assert query_idx.ndim == 1 and (query_idx >= 0).all() and (query_idx < N).all()
+    out = np.empty((query_idx.shape[0], d), dtype=np.float64)
+    rc = lib.sta_oracle_attention(q.ctypes.data, k.ctypes.data, v.ctypes.data, d, _i3(grid), _i3(tile),
+                                  _i3(window_tokens), float(scale), query_idx.ctypes.data,
+                                  query_idx.shape[0], out.ctypes.data)
+    if rc != 0:
+        raise MemoryError("oracle attention failed")
+    return out
+
+
+def attention_bh(q, k, v, grid, tile, window_tokens_per_head, scale=None, query_idx=None):
+    """[B, H, N, d] inputs, per-head windows (tokens) -> [B, H, nq, d] fp64."""
+    B, H = q.shape[0], q.shape[1]
+    outs = []
+    for b in range(B):
+        row = []
+        for h in range(H):
+            row.append(attention(q[b, h], k[b, h], v[b, h], grid, tile, window_tokens_per_head[h],
+                                 scale=scale, query_idx=query_idx))
+        outs.append(np.stack(row))
+    return np.stack(outs)
+
+
+def probs(q, k, grid, tile, window_tokens, i, scale=None):
+    """Row i of A = softmax(S + M) over all N keys, and its sum."""
+    lib = _load()
+    q, k = _f32(q), _f32(k)
+    N, d = q.shape
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    p = np.empty(N, dtype=np.float64)
+    s = ctypes.c_double(0.0)
+    lib.sta_oracle_probs(q.ctypes.data, k.ctypes.data, d, _i3(grid), _i3(tile), _i3(window_tokens),
+                         float(scale), int(i), p.ctypes.data, ctypes.addressof(s))
+    return p, float(s.value)
+
+
+def tile_order(grid, tile):
+    """order[slot] = raster index of the token stored at tiled slot."""
+    lib = _load()
+    N = int(grid[0]) * int(grid[1]) * int(grid[2])
+    order = np.empty(N, dtype=np.int64)
+    if lib.sta_oracle_tile_order(_i3(grid), _i3(tile), order.ctypes.data) != 0:
+        raise ValueError("grid is not a multiple of tile")
+    return order
+
+
+def _permute(fn_name, x, grid, tile):
+    lib = _load()
+    x = np.ascontiguousarray(x)
+    N = int(grid[0]) * int(grid[1]) * int(grid[2])
+    assert x.ndim >= 2 and x.shape[-2] == N, "expect [..., N, d]"
+    row_bytes = x.shape[-1] * x.dtype.itemsize
+    outer = int(np.prod(x.shape[:-2])) if x.ndim > 2 else 1
+    out = np.empty_like(x)
+    rc = getattr(lib, fn_name)(x.ctypes.data, out.ctypes.data, outer, row_bytes, _i3(grid), _i3(tile))
+    if rc != 0:
+        raise ValueError("grid is not a multiple of tile")
+    return out
+
+
+def tile_permute(x, grid, tile):
+    """Raster [..., N, d] -> tile-contiguous [..., N, d] (whole rows move)."""
+    return _permute("sta_oracle_tile_permute", x, grid, tile)
+
+
+def untile(x, grid, tile):
+    """Inverse of tile_permute."""
+    return _permute("sta_oracle_untile", x, grid, tile)
+
+
+def key_tiles(grid, tile, window_tokens):
+    """(counts[n], lists[n][n]) from the collapsed token predicate; -1 padded."""
+    lib = _load()
+    n = (int(grid[0]) // int(tile[0])) * (int(grid[1]) // int(tile[1])) * (int(grid[2]) // int(tile[2]))
+    counts = np.empty(n, dtype=np.int32)
+    lists = np.empty((n, n), dtype=np.int32)
+    if lib.sta_oracle_key_tiles(_i3(grid), _i3(tile), _i3(window_tokens), counts.ctypes.data,
+                                lists.ctypes.data) != 0:
+        raise ValueError("grid is not a multiple of tile")
+    return counts, lists
+
+
+def block_census(grid, tile, window_tokens):
+    """(dense, mixed, empty) block counts by brute force over all token pairs."""
+    lib = _load()
+    vals = [ctypes.c_int64(0) for _ in range(3)]
+    if lib.sta_oracle_block_census(_i3(grid), _i3(tile), _i3(window_tokens),
+                                   *[ctypes.addressof(v) for v in vals]) != 0:
+        raise ValueError("grid is not a multiple of tile")
+    return tuple(int(v.value) for v in vals)

@@ -1,0 +1,329 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against something
+other than itself -- values the paper prints, closed forms, library routines
+on special cases, brute-force characterisations written differently.  No GPU.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import sta_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _rows(name):
+    out = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                out.append(line.split())
+    return out
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape).astype(np.float32)
+
+
+def _dense_softmax_attention(q, k, v, scale):
+    """Library one-liner for unmasked attention (numpy fp64 matmuls)."""
+    q, k, v = (x.astype(np.float64) for x in (q, k, v))
+    s = (q @ k.T) * scale
+    s = s - s.max(axis=1, keepdims=True)
+    a = np.exp(s)
+    a /= a.sum(axis=1, keepdims=True)
+    return a @ v
+
+
+# --------------------------------------------------------------------------
+# Whole attention: special cases that reduce to a library routine
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("grid,tile", [((4, 6, 4), (2, 3, 2)), ((1, 8, 12), (1, 4, 4)), ((6, 4, 4), (2, 2, 2))])
+def test_full_window_equals_dense_softmax_attention(grid, tile):
+    """Window covering the whole grid => textbook softmax(QK^T/sqrt(d))V (Eq. 1 with M = 0)."""
+    N, d = int(np.prod(grid)), 16
+    q, k, v = _rand((N, d), 1), _rand((N, d), 2), _rand((N, d), 3)
+    out = orc.attention(q, k, v, grid, tile, window_tokens=grid)
+    ref = _dense_softmax_attention(q, k, v, 1.0 / np.sqrt(d))
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_full_window_when_window_exceeds_grid():
+    grid, tile = (4, 4, 6), (2, 2, 2)
+    N, d = int(np.prod(grid)), 8
+    q, k, v = _rand((N, d), 4), _rand((N, d), 5), _rand((N, d), 6)
+    out = orc.attention(q, k, v, grid, tile, window_tokens=(8, 12, 14))
+    ref = _dense_softmax_attention(q, k, v, 1.0 / np.sqrt(d))
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_unit_window_is_block_diagonal_per_tile_attention():
+    """Window of one tile: each tile attends only to itself => independent dense
+    attention over the tile's own tokens, gathered by coordinates."""
+    grid, tile = (4, 6, 6), (2, 3, 2)
+    N, d = int(np.prod(grid)), 12
+    q, k, v = _rand((N, d), 7), _rand((N, d), 8), _rand((N, d), 9)
+    out = orc.attention(q, k, v, grid, tile, window_tokens=tile)
+    coords = np.stack(np.unravel_index(np.arange(N), grid), axis=1)
+    tile_of = coords // np.array(tile)
+    for tc in itertools.product(*[range(g // t) for g, t in zip(grid, tile)]):
+        idx = np.nonzero((tile_of == np.array(tc)).all(axis=1))[0]
+        assert idx.size == np.prod(tile)
+        ref = _dense_softmax_attention(q[idx], k[idx], v[idx], 1.0 / np.sqrt(d))
+        np.testing.assert_allclose(out[idx], ref, rtol=1e-12, atol=1e-13)
+
+
+def test_scale_argument_and_default():
+    """Default scale is 1/sqrt(d_k) (Eq. 1); an explicit scale multiplies QK^T."""
+    grid, tile = (2, 4, 4), (1, 2, 2)
+    N, d = int(np.prod(grid)), 8
+    q, k, v = _rand((N, d), 10), _rand((N, d), 11), _rand((N, d), 12)
+    a = orc.attention(q, k, v, grid, tile, grid)
+    b = orc.attention(q * 2.0, k, v, grid, tile, grid, scale=0.5 / np.sqrt(d))
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-13)
+    c = orc.attention(q, k, v, grid, tile, grid, scale=0.3)
+    np.testing.assert_allclose(c, _dense_softmax_attention(q, k, v, 0.3), rtol=1e-12, atol=1e-13)
+
+
+def test_operands_not_transposed_or_swapped():
+    """Distinct roles of Q, K, V: swapping K and V, or Q and K, changes the result
+    in the way the dense library routine says."""
+    grid, tile = (2, 2, 4), (1, 1, 2)
+    N, d = int(np.prod(grid)), 4
+    q, k, v = _rand((N, d), 13), _rand((N, d), 14), _rand((N, d), 15)
+    np.testing.assert_allclose(orc.attention(k, q, v, grid, tile, grid),
+                               _dense_softmax_attention(k, q, v, 0.5), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(orc.attention(q, v, k, grid, tile, grid),
+                               _dense_softmax_attention(q, v, k, 0.5), rtol=1e-12, atol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# Softmax invariants
+# --------------------------------------------------------------------------
+def test_softmax_rows_sum_to_one_and_vanish_outside_window():
+    grid, tile, win = (4, 6, 6), (2, 2, 2), (2, 6, 2)
+    N, d = int(np.prod(grid)), 8
+    q, k = _rand((N, d), 16) * 3.0, _rand((N, d), 17) * 3.0
+    for i in (0, 17, 71, N - 1):
+        p, s = orc.probs(q, k, grid, tile, win, i)
+        assert abs(s - 1.0) <= 1e-14
+        assert abs(p.sum() - 1.0) <= 1e-13
+        assert (p >= 0).all()
+        qc = np.unravel_index(i, grid)
+        for j in range(N):
+            kc = np.unravel_index(j, grid)
+            assert (p[j] > 0) == orc.keep(qc, kc, grid, win, tile)
+
+
+def test_constant_v_and_convex_hull():
+    grid, tile, win = (2, 6, 8), (1, 2, 2), (1, 6, 6)
+    N, d = int(np.prod(grid)), 6
+    q, k = _rand((N, d), 18), _rand((N, d), 19)
+    vconst = np.tile(np.linspace(-1, 1, d, dtype=np.float32), (N, 1))
+    out = orc.attention(q, k, vconst, grid, tile, win)
+    np.testing.assert_allclose(out, vconst.astype(np.float64), rtol=0, atol=1e-14)
+    v = _rand((N, d), 20)
+    out = orc.attention(q, k, v, grid, tile, win)
+    assert (out <= v.max(axis=0) + 1e-12).all() and (out >= v.min(axis=0) - 1e-12).all()
+
+
+# --------------------------------------------------------------------------
+# Kept set, read straight out of the attention output (Q = 0, one-hot V)
+# --------------------------------------------------------------------------
+def _axis_box_by_shifting(qt, n, w):
+    """Independent characterisation of the border rule (Sec. 2.1: window centres
+    shift at the borders so every query keeps a constant number of keys): the
+    interval of 2*(w//2)+1 tiles centred on qt, slid the least distance needed
+    to lie inside [0, n-1]; if it cannot fit, the whole axis."""
+    half = w // 2
+    size = 2 * half + 1
+    if size >= n:
+        return set(range(n))
+    lo = qt - half
+    while lo < 0:
+        lo += 1
+    while lo + size - 1 > n - 1:
+        lo -= 1
+    return set(range(lo, lo + size))
+
+
+@pytest.mark.parametrize("grid,tile,win_tiles", [
+    ((4, 6, 10), (1, 2, 2), (3, 3, 3)),
+    ((4, 6, 10), (2, 2, 2), (1, 3, 5)),
+    ((6, 4, 8), (1, 1, 2), (5, 1, 3)),
+    ((1, 12, 12), (1, 2, 2), (1, 3, 3)),
+    ((3, 6, 6), (1, 2, 2), (2, 4, 3)),      # even window entries: follow the algorithm literally
+])
+def test_kept_set_read_from_output_matches_shifted_window(grid, tile, win_tiles):
+    tg = [g // t for g, t in zip(grid, tile)]
+    n = int(np.prod(tg))
+    N = int(np.prod(grid))
+    coords = np.stack(np.unravel_index(np.arange(N), grid), axis=1)
+    tile_id = np.ravel_multi_index((coords // np.array(tile)).T, tg)
+    d = n
+    q = np.zeros((N, d), np.float32)
+    k = _rand((N, d), 21)
+    v = np.zeros((N, d), np.float32)
+    v[np.arange(N), tile_id] = 1.0
+    win_tokens = orc.window_tiles_to_tokens(win_tiles, tile)
+    out = orc.attention(q, k, v, grid, tile, win_tokens)
+    for i in range(N):
+        qt = np.unravel_index(tile_id[i], tg)
+        boxes = [_axis_box_by_shifting(qt[a], tg[a], win_tiles[a]) for a in range(3)]
+        kept = {int(np.ravel_multi_index(c, tg)) for c in itertools.product(*boxes)}
+        expect = np.zeros(n)
+        expect[list(kept)] = 1.0 / len(kept)
+        np.testing.assert_allclose(out[i], expect, rtol=0, atol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# Counts the paper prints
+# --------------------------------------------------------------------------
+def test_table1_sta_block_ratios():
+    """Table 1 STA rows / Theorem 2 at video 48^3, tile 4^3."""
+    grid, tile = (48, 48, 48), (4, 4, 4)
+    for w, dense_pct, mixed_pct in _rows("table1_sta_block_ratios.txt"):
+        w = int(w)
+        counts, _ = orc.key_tiles(grid, tile, (w, w, w))
+        n = counts.size
+        assert n == 12 ** 3
+        dense = int(counts.sum())
+        assert dense == (w // 4) ** 3 * 12 ** 3                 # Theorem 2
+        assert round(100.0 * dense / n ** 2, 2) == float(dense_pct)
+        assert float(mixed_pct) == 0.0
+
+
+def test_hunyuan_grid_sparsities():
+    """91.00 / 58.33 / 75.00 % on the (30,48,80) grid with tile (6,8,8); every query
+    tile keeps the same number of key tiles."""
+    grid, tile = (30, 48, 80), (6, 8, 8)
+    for wt, wh, ww, pct in _rows("sparsity_hunyuan_grid.txt"):
+        win = (int(wt), int(wh), int(ww))
+        counts, lists = orc.key_tiles(grid, tile, win)
+        assert counts.size == 300
+        per_q = (win[0] // 6) * (win[1] // 8) * (win[2] // 8)
+        assert (counts == per_q).all()
+        sparsity = 100.0 * (1.0 - counts.sum() / 300.0 ** 2)
+        assert abs(sparsity - float(pct)) < 0.005
+        for qt in range(300):                                       # a tile always keeps itself
+            assert qt in lists[qt, :counts[qt]]
+
+
+def test_fig4_nine_dense_blocks_per_query_tile():
+    (th, tw, wh, ww, nblocks, br, bc), = _rows("fig4_2d_tile2_window6.txt")
+    tile = (1, int(th), int(tw))
+    grid = (1, 12, 16)
+    counts, _ = orc.key_tiles(grid, tile, (1, int(wh), int(ww)))
+    assert (counts == int(nblocks)).all()
+    assert tile[1] * tile[2] == int(br) == int(bc)
+    dense, mixed, empty = orc.block_census(grid, tile, (1, int(wh), int(ww)))
+    assert dense == int(nblocks) * counts.size and mixed == 0
+
+
+@pytest.mark.parametrize("grid,tile,win", [
+    ((1, 24, 24), (1, 4, 4), (1, 12, 12)),      # Fig. 3 setting: image 24x24, window 12x12, tile 4x4
+    ((6, 8, 8), (2, 2, 2), (2, 6, 6)),
+    ((4, 6, 9), (2, 3, 3), (6, 6, 9)),
+    ((6, 6, 6), (1, 2, 3), (4, 4, 6)),          # even tile-window
+])
+def test_no_mixed_blocks_by_brute_force(grid, tile, win):
+    """Theorem 2: every block is dense or empty; dense count = sum of per-tile list sizes."""
+    dense, mixed, empty = orc.block_census(grid, tile, win)
+    counts, _ = orc.key_tiles(grid, tile, win)
+    n = counts.size
+    assert mixed == 0
+    assert dense == counts.sum()
+    assert dense + empty == n * n
+
+
+def test_one_axis_border_placement_enumeration():
+    """1-D enumeration: for every n <= 10, window w <= n + 2 and query tile, the kept
+    interval is contiguous, has size min(n, 2*(w//2)+1), contains the query tile, lies
+    in the grid, and equals [q-half, q+half] whenever that fits."""
+    for n in range(1, 11):
+        for w in range(1, n + 3):
+            counts, lists = orc.key_tiles((1, 1, n), (1, 1, 1), (1, 1, w))
+            half = w // 2
+            for qt in range(n):
+                ks = lists[qt, :counts[qt]].tolist()
+                assert ks == list(range(ks[0], ks[0] + len(ks)))
+                assert len(ks) == min(n, 2 * half + 1)
+                assert qt in ks and ks[0] >= 0 and ks[-1] <= n - 1
+                if qt - half >= 0 and qt + half <= n - 1:
+                    assert ks == list(range(qt - half, qt + half + 1))
+                assert set(ks) == _axis_box_by_shifting(qt, n, w)
+
+
+def test_mask_is_not_symmetric_at_borders():
+    """Border clamp: tile 0 keeps tile 2 (window 3 of 4 tiles) but tile 2 does not keep tile 0."""
+    grid, tile, win = (1, 1, 4), (1, 1, 1), (1, 1, 3)
+    assert orc.keep((0, 0, 0), (0, 0, 2), grid, win, tile)
+    assert not orc.keep((0, 0, 2), (0, 0, 0), grid, win, tile)
+
+
+def test_axes_are_not_mixed_up():
+    """Different window per axis on a non-cubic grid: the kept box has the per-axis sizes
+    in the right order."""
+    grid, tile, win_tiles = (8, 10, 12), (2, 2, 2), (1, 3, 5)
+    counts, lists = orc.key_tiles(grid, tile, orc.window_tiles_to_tokens(win_tiles, tile))
+    tg = (4, 5, 6)
+    for qt in range(counts.size):
+        c = np.array(np.unravel_index(lists[qt, :counts[qt]], tg))
+        spans = [int(c[a].max() - c[a].min() + 1) for a in range(3)]
+        assert spans == [1, 3, 5]
+
+
+# --------------------------------------------------------------------------
+# Permutation
+# --------------------------------------------------------------------------
+def test_fig7_order_9x9_tile3x3():
+    want = np.array([int(x) for row in _rows("fig7_9x9_tile3x3_order.txt") for x in row])
+    got = orc.tile_order((1, 9, 9), (1, 3, 3))
+    np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("grid,tile", [((4, 6, 8), (2, 3, 4)), ((18, 24, 24), (6, 8, 8)), ((1, 16, 8), (1, 8, 8)),
+                                       ((3, 5, 7), (3, 5, 7)), ((3, 5, 7), (1, 1, 1))])
+def test_permutation_is_bijection_tiles_contiguous_and_roundtrip(grid, tile):
+    N = int(np.prod(grid))
+    P = int(np.prod(tile))
+    order = orc.tile_order(grid, tile)
+    assert sorted(order.tolist()) == list(range(N))
+    tg = [g // t for g, t in zip(grid, tile)]
+    coords = np.stack(np.unravel_index(order, grid), axis=1)
+    tid = np.ravel_multi_index((coords // np.array(tile)).T, tg)
+    np.testing.assert_array_equal(tid, np.repeat(np.arange(N // P), P))      # tile tau occupies [tau*P, (tau+1)*P)
+    intra = np.ravel_multi_index((coords % np.array(tile)).T, tile)
+    np.testing.assert_array_equal(intra, np.tile(np.arange(P), N // P))      # row-major inside the tile
+    x = _rand((2, 3, N, 4), 22)
+    y = orc.tile_permute(x, grid, tile)
+    np.testing.assert_array_equal(y, x[:, :, order, :])
+    np.testing.assert_array_equal(orc.untile(y, grid, tile), x)
+    xb = (np.arange(2 * N * 6, dtype=np.uint16)).reshape(2, N, 6)               # 2-byte rows move whole
+    np.testing.assert_array_equal(orc.untile(orc.tile_permute(xb, grid, tile), grid, tile), xb)
+
+
+def test_permutation_equivariance_of_attention():
+    """Attention over tile-ordered tokens, computed by the dense library routine per
+    kept set, equals the raster-order oracle gathered into tile order."""
+    grid, tile, win = (2, 4, 6), (1, 2, 2), (1, 6, 2)
+    N, d = int(np.prod(grid)), 8
+    q, k, v = _rand((N, d), 23), _rand((N, d), 24), _rand((N, d), 25)
+    out = orc.attention(q, k, v, grid, tile, win)
+    order = orc.tile_order(grid, tile)
+    counts, lists = orc.key_tiles(grid, tile, win)
+    P = int(np.prod(tile))
+    qt_, kt_, vt_ = q[order], k[order], v[order]
+    for qt in range(counts.size):
+        keys = np.concatenate([np.arange(t * P, (t + 1) * P) for t in lists[qt, :counts[qt]]])
+        ref = _dense_softmax_attention(qt_[qt * P:(qt + 1) * P], kt_[keys], vt_[keys], 1.0 / np.sqrt(d))
+        np.testing.assert_allclose(out[order][qt * P:(qt + 1) * P], ref, rtol=1e-12, atol=1e-13)
+
+
+def test_non_multiple_grid_is_rejected():
+    with pytest.raises(ValueError):
+        orc.tile_order((5, 4, 4), (2, 2, 2))
+    with pytest.raises(ValueError):
+        orc.key_tiles((4, 4, 5), (2, 2, 2), (2, 2, 2))
