@@ -1,0 +1,129 @@
+/*
+ * sta.h -- C ABI of the Sliding Tile Attention (STA) forward path for AMD
+ * MI355X (gfx950).
+ *
+ * Conventions that hold for every entry point
+ *   - The return value is an sta_status.  Nothing throws, aborts or prints.
+ *     Argument checks happen on the host before any launch; a failed check
+ *     launches nothing.
+ *   - Pointers named dev_* / *_tiled / src / dst are DEVICE pointers owned by
+ *     the caller; `grid`, `tile`, `window_tiles` and friends are HOST pointers
+ *     that are read during the call and may be freed on return.
+ *   - Tensors are contiguous [B, H, N, D] (batch, head, token, channel) with
+ *     N = grid[0]*grid[1]*grid[2].  "raster" order puts token (t,h,w) at
+ *     n = (t*grid[1] + h)*grid[2] + w.  "tiled" order puts it at
+ *     n = tile_id*P + intra_id with tile_id row-major over the tile grid
+ *     (grid[a]/tile[a] per axis), intra_id row-major inside the tile and
+ *     P = tile[0]*tile[1]*tile[2]  (Sec. 3.1: tokens of one tile get
+ *     consecutive sequence indices; appendix "Tiling in STA").
+ *   - All device work is enqueued on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = default stream) and is asynchronous.
+ *   - The library allocates no device memory and keeps no state.
+ *   - 2D (image) STA is the 3D case with grid[0] = tile[0] = window[0] = 1.
+ */
+#ifndef STA_H
+#define STA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    STA_OK = 0,
+    STA_ERR_NULL = 1,        /* a required pointer is NULL */
+    STA_ERR_SHAPE = 2,       /* non-positive dimension, grid not a multiple of tile, size overflow */
+    STA_ERR_WINDOW = 3,      /* a window entry is < 1 */
+    STA_ERR_UNSUPPORTED = 4, /* (P, D, dtype) combination has no kernel */
+    STA_ERR_ALIAS = 5,       /* src == dst, or the output aliases an input */
+    STA_ERR_WORKSPACE = 6,   /* workspace missing or too small */
+    STA_ERR_HIP = 7          /* a HIP call or kernel launch failed */
+} sta_status;
+
+typedef enum { STA_BF16 = 0, STA_F32 = 1 } sta_dtype;
+
+/*
+ * Tile permutation (Sec. 3.1, appendix "Tiling in STA"): raster -> tiled.
+ * src, dst: device, [B, H, N, D], element types src_dt / dst_dt.  Whole
+ * token rows move; when the two types differ the value is converted on the
+ * way (f32 -> bf16 rounds to nearest even; bf16 -> f32 is exact).  D must be a
+ * multiple of 8.  src and dst must not overlap.
+ */
+int sta_tile_permute(const void *src, void *dst, int src_dt, int dst_dt,
+                     int B, int H, int D, const int grid[3], const int tile[3],
+                     void *hip_stream);
+
+/* Inverse permutation: tiled -> raster.  Same arguments and rules. */
+int sta_untile(const void *src, void *dst, int src_dt, int dst_dt,
+               int B, int H, int D, const int grid[3], const int tile[3],
+               void *hip_stream);
+
+/*
+ * STA forward (Eq. 1 with the mask of the appendix STA mask algorithm):
+ * for every head h and query tile, softmax(Q K^T * scale) V over the key
+ * tiles inside that head's window, the window being placed by the clamped
+ * centre rule.  q/k/v/o_tiled: device, bf16, [B, H, N, D] in TILED order.
+ * window_tiles: host, [H][3], window size in tiles per head (t, h, w), the
+ * same for every batch entry; an entry larger than the tile grid means the
+ * whole axis.  scale <= 0 selects 1/sqrt(D).  Arithmetic: bf16 inputs, fp32
+ * scores, softmax statistics and output accumulator, probabilities rounded
+ * to bf16 before the PV product, output rounded to bf16.
+ * Supported: D in {64, 128}; P a multiple of 32.  Anything else returns
+ * STA_ERR_UNSUPPORTED.  workspace: device scratch of at least
+ * sta_workspace_bytes(...) bytes (may be NULL when that is 0).
+ */
+int sta_forward(const void *q_tiled, const void *k_tiled, const void *v_tiled,
+                void *o_tiled, int B, int H, int D, const int grid[3],
+                const int tile[3], const int *window_tiles, float scale,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of device scratch sta_forward needs for this problem (0 if none). */
+size_t sta_workspace_bytes(int B, int H, int D, const int grid[3],
+                           const int tile[3]);
+
+/*
+ * Key-tile box of one query tile (appendix STA mask algorithm, in tile
+ * units): per axis a, half = window_tiles[a]/2 (integer), centre
+ * c = max(min(q_tile[a], grid_tiles[a]-1-half), half), kept key tiles are
+ * [c-half, c+half] clipped to the grid.  Host, pure integer.  lo/hi are
+ * inclusive.  Note an even window entry w keeps min(n, w+1) tiles, exactly as
+ * the algorithm's "<= W/2" test does.
+ */
+int sta_key_tile_box(const int grid_tiles[3], const int window_tiles[3],
+                     const int q_tile[3], int lo[3], int hi[3]);
+
+/*
+ * Test hook: the key-tile lists as the DEVICE code computes them (the same
+ * device function the attention kernel calls).  dev_counts: device int32
+ * [H][n]; dev_lists: device int32 [H][n][n], ascending tile ids, -1 padded;
+ * n = number of tiles.
+ */
+int sta_dump_key_tiles(int H, const int grid[3], const int tile[3],
+                       const int *window_tiles, int32_t *dev_counts,
+                       int32_t *dev_lists, void *hip_stream);
+
+/*
+ * Window in tokens (the paper's notation, e.g. (18,24,24)) -> window in
+ * tiles.  STA_ERR_WINDOW unless every entry is a positive multiple of the
+ * tile size (Sec. 3.1 assumes W is an integer multiple of T).
+ */
+int sta_window_tokens_to_tiles(const int window_tokens[3], const int tile[3],
+                               int out_tiles[3]);
+
+/*
+ * Work model used for reporting (Sec. 4.1 counts only kept blocks):
+ * 4 * P^2 * D flop per (query tile, key tile) pair, summed over heads and
+ * batch.  Returns 0.0 on invalid arguments.
+ */
+double sta_kept_flops(int B, int H, int D, const int grid[3], const int tile[3],
+                      const int *window_tiles);
+
+const char *sta_strerror(int status);
+int sta_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STA_H */

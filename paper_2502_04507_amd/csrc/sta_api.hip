@@ -1,0 +1,265 @@
+// C ABI of libsta: argument checking, host-side geometry, kernel dispatch.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/sta.h"
+#include "sta_geometry.h"
+#include "sta_internal.h"
+
+namespace {
+
+struct Shape {
+    int64_t N, P, n_tiles;
+    int n[3];
+};
+
+// Validates B, H, D, grid, tile and fills the derived sizes.
+int check_shape(int B, int H, int D, const int grid[3], const int tile[3], Shape *s)
+{
+    if (!grid || !tile) return STA_ERR_NULL;
+    if (B <= 0 || H <= 0 || D <= 0) return STA_ERR_SHAPE;
+    int64_t N = 1, P = 1, nt = 1;
+    for (int a = 0; a < 3; ++a) {
+        if (grid[a] <= 0 || tile[a] <= 0 || grid[a] % tile[a] != 0) return STA_ERR_SHAPE;
+        s->n[a] = grid[a] / tile[a];
+        if (s->n[a] > 30000) return STA_ERR_SHAPE;
+        N *= grid[a];
+        P *= tile[a];
+        nt *= s->n[a];
+        if (N > (int64_t)1 << 30 || P > (int64_t)1 << 20) return STA_ERR_SHAPE;
+    }
+    // element count of one tensor must stay addressable with comfortable margin
+    const long double total = (long double)B * H * (long double)N * D;
+    if (total > 9.0e15L) return STA_ERR_SHAPE;
+    if ((int64_t)B * H > 0x7fffffff / (nt > 0 ? nt : 1)) return STA_ERR_SHAPE;
+    s->N = N;
+    s->P = P;
+    s->n_tiles = nt;
+    return STA_OK;
+}
+
+bool valid_dtype(int dt) { return dt == STA_BF16 || dt == STA_F32; }
+
+size_t elem_size(int dt) { return dt == STA_F32 ? 4 : 2; }
+
+bool ranges_overlap(const void *a, size_t abytes, const void *b, size_t bbytes)
+{
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + bbytes && b0 < a0 + abytes;
+}
+
+uint32_t magic_of(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); }
+
+int permute_common(const void *src, void *dst, int src_dt, int dst_dt, int B, int H, int D, const int grid[3],
+                   const int tile[3], void *hip_stream, bool to_tiled)
+{
+    if (!src || !dst) return STA_ERR_NULL;
+    Shape s;
+    if (int rc = check_shape(B, H, D, grid, tile, &s)) return rc;
+    if (!valid_dtype(src_dt) || !valid_dtype(dst_dt)) return STA_ERR_UNSUPPORTED;
+    if (D % 8 != 0) return STA_ERR_UNSUPPORTED;
+    const size_t elems = (size_t)B * H * s.N * D;
+    if (ranges_overlap(src, elems * elem_size(src_dt), dst, elems * elem_size(dst_dt))) return STA_ERR_ALIAS;
+
+    sta::PermuteParams p;
+    p.N = (uint32_t)s.N;
+    p.cpr = (uint32_t)(D / 8);
+    p.L_h = grid[1];
+    p.L_w = grid[2];
+    p.T_t = tile[0];
+    p.T_h = tile[1];
+    p.T_w = tile[2];
+    p.n_h = s.n[1];
+    p.n_w = s.n[2];
+    p.n_tiles = (uint32_t)s.n_tiles;
+    const uint64_t cpt = (uint64_t)s.P * p.cpr;
+    p.seg = p.T_w * p.cpr;
+    // exactness condition of the multiply-high division used by the kernel
+    if (cpt * p.seg >= ((uint64_t)1 << 32) || cpt * p.T_h >= ((uint64_t)1 << 32)) return STA_ERR_SHAPE;
+    p.chunks_per_tile = (uint32_t)cpt;
+    p.seg_magic = magic_of(p.seg);
+    p.T_h_magic = magic_of(p.T_h);
+    const uint32_t blocks = (uint32_t)((int64_t)B * H * s.n_tiles);
+    hipError_t e = sta::launch_permute(src, dst, src_dt == STA_F32, dst_dt == STA_F32, to_tiled, p, blocks,
+                                       static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? STA_OK : STA_ERR_HIP;
+}
+
+int check_windows(int H, const int *window_tiles)
+{
+    if (!window_tiles) return STA_ERR_NULL;
+    for (int i = 0; i < 3 * H; ++i)
+        if (window_tiles[i] < 1) return STA_ERR_WINDOW;
+    return STA_OK;
+}
+
+void fill_window_table(sta::WindowTable *t, const int *window_tiles, int head_base, int heads, const int n[3])
+{
+    for (int h = 0; h < heads; ++h)
+        for (int a = 0; a < 3; ++a) {
+            const int w = window_tiles[3 * (head_base + h) + a];
+            t->w[h][a] = (uint16_t)(w < 2 * n[a] ? w : 2 * n[a]);   // >= 2n-1 already means the whole axis
+        }
+}
+
+sta::FwdParams make_fwd_params(const Shape &s, int H, float scale_log2e)
+{
+    sta::FwdParams p;
+    p.N = (uint32_t)s.N;
+    p.P = (uint32_t)s.P;
+    p.n_t = s.n[0];
+    p.n_h = s.n[1];
+    p.n_w = s.n[2];
+    p.n_tiles = (uint32_t)s.n_tiles;
+    p.H = H;
+    p.head_base = 0;
+    p.heads = 0;
+    p.scale_log2e = scale_log2e;
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sta_tile_permute(const void *src, void *dst, int src_dt, int dst_dt, int B, int H, int D, const int grid[3],
+                     const int tile[3], void *hip_stream)
+{
+    return permute_common(src, dst, src_dt, dst_dt, B, H, D, grid, tile, hip_stream, true);
+}
+
+int sta_untile(const void *src, void *dst, int src_dt, int dst_dt, int B, int H, int D, const int grid[3],
+               const int tile[3], void *hip_stream)
+{
+    return permute_common(src, dst, src_dt, dst_dt, B, H, D, grid, tile, hip_stream, false);
+}
+
+size_t sta_workspace_bytes(int, int, int, const int *, const int *) { return 0; }
+
+int sta_forward(const void *q_tiled, const void *k_tiled, const void *v_tiled, void *o_tiled, int B, int H, int D,
+                const int grid[3], const int tile[3], const int *window_tiles, float scale, void *workspace,
+                size_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!q_tiled || !k_tiled || !v_tiled || !o_tiled) return STA_ERR_NULL;
+    Shape s;
+    if (int rc = check_shape(B, H, D, grid, tile, &s)) return rc;
+    if (int rc = check_windows(H, window_tiles)) return rc;
+    if (!sta::forward_supported((int)s.P, D)) return STA_ERR_UNSUPPORTED;
+    const size_t bytes = (size_t)B * H * s.N * D * 2;
+    if (ranges_overlap(o_tiled, bytes, q_tiled, bytes) || ranges_overlap(o_tiled, bytes, k_tiled, bytes) ||
+        ranges_overlap(o_tiled, bytes, v_tiled, bytes))
+        return STA_ERR_ALIAS;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+    sta::FwdParams p = make_fwd_params(s, H, scale * 1.4426950408889634f);
+
+    // Per-head windows travel in the kernel arguments; heads are launched in chunks.
+    int max_heads = sta::kMaxHeadsPerLaunch;
+    if ((int64_t)B * max_heads > 65535) max_heads = 65535 / B;
+    if (max_heads < 1) return STA_ERR_SHAPE;
+    for (int hb = 0; hb < H; hb += max_heads) {
+        const int heads = (H - hb) < max_heads ? (H - hb) : max_heads;
+        sta::WindowTable win;
+        fill_window_table(&win, window_tiles, hb, heads, s.n);
+        p.head_base = hb;
+        p.heads = heads;
+        hipError_t e = sta::launch_forward(q_tiled, k_tiled, v_tiled, o_tiled, B, D, p, win,
+                                           static_cast<hipStream_t>(hip_stream));
+        if (e != hipSuccess) return STA_ERR_HIP;
+    }
+    return STA_OK;
+}
+
+int sta_key_tile_box(const int grid_tiles[3], const int window_tiles[3], const int q_tile[3], int lo[3], int hi[3])
+{
+    if (!grid_tiles || !window_tiles || !q_tile || !lo || !hi) return STA_ERR_NULL;
+    for (int a = 0; a < 3; ++a) {
+        if (grid_tiles[a] <= 0 || q_tile[a] < 0 || q_tile[a] >= grid_tiles[a]) return STA_ERR_SHAPE;
+        if (window_tiles[a] < 1) return STA_ERR_WINDOW;
+    }
+    for (int a = 0; a < 3; ++a) {
+        const int n = grid_tiles[a];
+        const int w = window_tiles[a] < 2 * n ? window_tiles[a] : 2 * n;
+        const StaAxisRange r = sta_axis_range(n, w, q_tile[a]);
+        lo[a] = r.lo;
+        hi[a] = r.hi;
+    }
+    return STA_OK;
+}
+
+int sta_dump_key_tiles(int H, const int grid[3], const int tile[3], const int *window_tiles, int32_t *dev_counts,
+                       int32_t *dev_lists, void *hip_stream)
+{
+    if (!dev_counts || !dev_lists) return STA_ERR_NULL;
+    Shape s;
+    if (int rc = check_shape(1, H, 8, grid, tile, &s)) return rc;
+    if (int rc = check_windows(H, window_tiles)) return rc;
+    sta::FwdParams p = make_fwd_params(s, H, 1.f);
+    for (int hb = 0; hb < H; hb += sta::kMaxHeadsPerLaunch) {
+        const int heads = (H - hb) < sta::kMaxHeadsPerLaunch ? (H - hb) : sta::kMaxHeadsPerLaunch;
+        sta::WindowTable win;
+        fill_window_table(&win, window_tiles, hb, heads, s.n);
+        p.head_base = hb;
+        p.heads = heads;
+        if (sta::launch_dump_key_tiles(p, win, dev_counts, dev_lists, static_cast<hipStream_t>(hip_stream)) !=
+            hipSuccess)
+            return STA_ERR_HIP;
+    }
+    return STA_OK;
+}
+
+int sta_window_tokens_to_tiles(const int window_tokens[3], const int tile[3], int out_tiles[3])
+{
+    if (!window_tokens || !tile || !out_tiles) return STA_ERR_NULL;
+    for (int a = 0; a < 3; ++a) {
+        if (tile[a] <= 0) return STA_ERR_SHAPE;
+        if (window_tokens[a] <= 0 || window_tokens[a] % tile[a] != 0) return STA_ERR_WINDOW;
+    }
+    for (int a = 0; a < 3; ++a) out_tiles[a] = window_tokens[a] / tile[a];
+    return STA_OK;
+}
+
+double sta_kept_flops(int B, int H, int D, const int grid[3], const int tile[3], const int *window_tiles)
+{
+    Shape s;
+    if (check_shape(B, H, D, grid, tile, &s) != STA_OK) return 0.0;
+    if (check_windows(H, window_tiles) != STA_OK) return 0.0;
+    double pairs = 0.0;
+    for (int h = 0; h < H; ++h) {
+        // the box is a product of per-axis ranges, so the pair count factorises
+        double per_head = 1.0;
+        for (int a = 0; a < 3; ++a) {
+            const int n = s.n[a];
+            const int w = window_tiles[3 * h + a] < 2 * n ? window_tiles[3 * h + a] : 2 * n;
+            long sum = 0;
+            for (int qa = 0; qa < n; ++qa) {
+                const StaAxisRange r = sta_axis_range(n, w, qa);
+                sum += r.hi - r.lo + 1;
+            }
+            per_head *= (double)sum;
+        }
+        pairs += per_head;
+    }
+    return 4.0 * (double)s.P * (double)s.P * (double)D * pairs * (double)B;
+}
+
+const char *sta_strerror(int status)
+{
+    switch (status) {
+    case STA_OK: return "ok";
+    case STA_ERR_NULL: return "required pointer is NULL";
+    case STA_ERR_SHAPE: return "invalid shape: non-positive dimension, grid not a multiple of tile, or too large";
+    case STA_ERR_WINDOW: return "invalid window: entries must be >= 1 (and multiples of the tile when given in tokens)";
+    case STA_ERR_UNSUPPORTED: return "unsupported combination of tile size, head dim or dtype";
+    case STA_ERR_ALIAS: return "source and destination buffers overlap";
+    case STA_ERR_WORKSPACE: return "workspace missing or too small";
+    case STA_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+    }
+}
+
+int sta_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,50 @@
+// Internal declarations shared by the translation units of libsta (GPU side only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sta {
+
+// ---- permutation -----------------------------------------------------------
+struct PermuteParams {
+    uint32_t N;                 // tokens per (b,h) slice
+    uint32_t cpr;               // 8-element chunks per token row (D / 8)
+    uint32_t L_h, L_w;          // grid
+    uint32_t T_t, T_h, T_w;     // tile
+    uint32_t n_h, n_w;          // tile grid (h, w)
+    uint32_t n_tiles;
+    uint32_t chunks_per_tile;   // P * cpr
+    uint32_t seg, seg_magic;    // T_w * cpr chunks per contiguous run, ceil(2^32/seg)
+    uint32_t T_h_magic;         // ceil(2^32 / T_h)
+};
+
+hipError_t launch_permute(const void *src, void *dst, bool src_f32, bool dst_f32, bool to_tiled,
+                          const PermuteParams &p, uint32_t blocks, hipStream_t stream);
+
+// ---- attention -------------------------------------------------------------
+constexpr int kMaxHeadsPerLaunch = 256;
+
+struct WindowTable {
+    uint16_t w[kMaxHeadsPerLaunch][3];   // window in tiles per head of this launch (clamped to 2*n)
+};
+
+struct FwdParams {
+    uint32_t N;            // tokens per head
+    uint32_t P;            // tokens per tile
+    uint32_t n_t, n_h, n_w;
+    uint32_t n_tiles;
+    uint32_t H;            // heads in the tensor
+    uint32_t head_base;    // first head of this launch
+    uint32_t heads;        // heads in this launch
+    float scale_log2e;     // softmax scale * log2(e)
+};
+
+// Returns hipErrorInvalidValue if no kernel instance exists for (P, D).
+hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, int B, int D,
+                          const FwdParams &p, const WindowTable &win, hipStream_t stream);
+bool forward_supported(int P, int D);
+
+hipError_t launch_dump_key_tiles(const FwdParams &p, const WindowTable &win, int32_t *counts,
+                                 int32_t *lists, hipStream_t stream);
+
+}  // namespace sta

@@ -1,0 +1,84 @@
+"""Helpers for the GPU parity tests: run the HIP chain through the C-ABI
+binding and evaluate the oracle on the same host tensors."""
+import numpy as np
+import torch
+
+import paper_2502_04507_amd as sta
+from oracle import sta_oracle as orc
+
+# Pass/fail contract for the bf16 attention output against the fp64 oracle.
+MAX_ABS_TOL = 2e-2
+MEAN_ABS_TOL = 2e-3
+# Stricter gates so that parity means something when outputs are small (the output
+# standard deviation is about sqrt(e / kept keys), i.e. of the order of the absolute
+# tolerances): relative Frobenius error and cosine similarity.  bf16 rounding of the
+# output alone gives a relative error of about 2^-9 / sqrt(3) = 1.1e-3.
+REL_FRO_TOL = 1e-2
+COSINE_MIN = 0.9999
+
+
+def gpu_chain(w, q, k, v, scale=0.0, device="cuda:0"):
+    """tile_permute(Q,K,V) -> sta_forward -> untile, all in the HIP library.
+    q, k, v: host tensors [B,H,N,D] in raster order (bf16 or f32).  Returns raster O (bf16, host)."""
+    qd, kd, vd = (x.to(device) for x in (q, k, v))
+    shape = qd.shape
+    qt, kt, vt, ot, o = (torch.empty(shape, dtype=torch.bfloat16, device=device) for _ in range(5))
+    sta.sta_tile_permute(qd, qt, w.grid, w.tile)
+    sta.sta_tile_permute(kd, kt, w.grid, w.tile)
+    sta.sta_tile_permute(vd, vt, w.grid, w.tile)
+    ot.fill_(float("nan"))
+    sta.sta_forward(qt, kt, vt, ot, w.grid, w.tile, w.window_tiles, scale=scale)
+    o.fill_(float("nan"))
+    sta.sta_untile(ot, o, w.grid, w.tile)
+    torch.cuda.synchronize()
+    return o.cpu()
+
+
+def oracle_rows(w, q, k, v, b, h, query_idx, scale=None):
+    """Oracle output for head (b,h) at the given raster query indices, fp64 [nq, D]."""
+    win_tokens = orc.window_tiles_to_tokens(w.window_tiles[h], w.tile)
+    return orc.attention(q[b, h].float().numpy(), k[b, h].float().numpy(), v[b, h].float().numpy(), w.grid, w.tile,
+                         win_tokens, scale=scale, query_idx=query_idx)
+
+
+def error_stats(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    diff = got - ref
+    return {
+        "max_abs": float(np.abs(diff).max()),
+        "mean_abs": float(np.abs(diff).mean()),
+        "rel_fro": float(np.linalg.norm(diff) / max(np.linalg.norm(ref), 1e-300)),
+        "cosine": float((got * ref).sum() / max(np.linalg.norm(got) * np.linalg.norm(ref), 1e-300)),
+    }
+
+
+def assert_parity(got, ref, label=""):
+    assert np.isfinite(np.asarray(got, dtype=np.float64)).all(), label + ": non-finite output"
+    st = error_stats(got, ref)
+    msg = "%s %s" % (label, st)
+    assert st["max_abs"] <= MAX_ABS_TOL, msg
+    assert st["mean_abs"] <= MEAN_ABS_TOL, msg
+    assert st["rel_fro"] <= REL_FRO_TOL, msg
+    assert st["cosine"] >= COSINE_MIN, msg
+    return st
+
+
+def stratified_query_sample(w, n_random, full_tiles, seed):
+    """Raster indices: every token of the given query tiles (row-major tile ids) plus
+    n_random tokens drawn uniformly."""
+    order = orc.tile_order(w.grid, w.tile)
+    P = w.P
+    idx = [order[t * P:(t + 1) * P] for t in full_tiles]
+    rng = np.random.default_rng(seed)
+    idx.append(rng.integers(0, w.N, size=n_random))
+    return np.unique(np.concatenate(idx)).astype(np.int64)
+
+
+def border_and_interior_tiles(w):
+    """Tile ids of two opposite corners, one edge/face tile and one interior tile."""
+    nt, nh, nw = w.tile_grid
+    rm = lambda a, b, c: (a * nh + b) * nw + c
+    picks = {rm(0, 0, 0), rm(nt - 1, nh - 1, nw - 1), rm(nt // 2, 0, nw // 2), rm(nt // 2, nh // 2, nw // 2),
+             rm(0, nh - 1, nw // 2)}
+    return sorted(picks)

@@ -1,0 +1,108 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its host-side logic (argument checks that return before
+any launch, key-tile box, token->tile window conversion, work model) agrees
+with the oracle and the paper's counts.  No compute call is made here."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2502_04507_amd as sta
+from oracle import sta_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+I3 = ctypes.c_int * 3
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "sta.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sta_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = sta.load_library()
+    names = _declared_functions()
+    assert len(names) >= 10
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(sta.EXPORTED_SYMBOLS) == names
+    assert sta.sta_version() >= 100
+
+
+def test_strerror_covers_all_codes():
+    msgs = {sta.sta_strerror(i) for i in range(8)}
+    assert len(msgs) == 8 and "unknown status" not in msgs
+    assert sta.sta_strerror(99) == "unknown status"
+
+
+def test_host_key_tile_box_matches_oracle_lists():
+    """Bit-exact: host box (ascending row-major enumeration) == oracle's collapsed token predicate."""
+    cases = [((30, 48, 80), (6, 8, 8), (3, 3, 3)), ((30, 48, 80), (6, 8, 8), (5, 3, 5)),
+             ((12, 48, 48), (6, 8, 8), (1, 3, 3)), ((1, 64, 64), (1, 8, 8), (1, 3, 3)),
+             ((8, 8, 12), (2, 2, 2), (2, 4, 7)), ((4, 6, 6), (2, 2, 2), (9, 1, 2)),
+             ((30, 48, 80), (6, 8, 8), (5, 6, 10))]
+    for grid, tile, wt in cases:
+        tg = [g // t for g, t in zip(grid, tile)]
+        counts, lists = orc.key_tiles(grid, tile, orc.window_tiles_to_tokens(wt, tile))
+        for qt, qc in enumerate(itertools.product(*[range(n) for n in tg])):
+            lo, hi = sta.sta_key_tile_box(tg, wt, qc)
+            ids = [int(np.ravel_multi_index(c, tg))
+                   for c in itertools.product(*[range(lo[a], hi[a] + 1) for a in range(3)])]
+            assert ids == lists[qt, :counts[qt]].tolist()
+
+
+def test_window_tokens_to_tiles():
+    assert sta.sta_window_tokens_to_tiles((18, 24, 24), (6, 8, 8)) == (3, 3, 3)     # Sec. 4.3
+    assert sta.sta_window_tokens_to_tiles((30, 40, 40), (6, 8, 8)) == (5, 5, 5)
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_window_tokens_to_tiles((19, 25, 25), (6, 8, 8))
+    assert e.value.status == 3
+    with pytest.raises(sta.StaError):
+        sta.sta_window_tokens_to_tiles((0, 8, 8), (6, 8, 8))
+
+
+def test_kept_flops_model_matches_paper_scaling():
+    """Work is 4*P^2*D per kept pair; kept fractions 27/300 and 125/300 (Table 2 scales its
+    work column by exactly these)."""
+    grid, tile = (30, 48, 80), (6, 8, 8)
+    dense = sta.sta_kept_flops(1, 24, 128, grid, tile, [(5, 6, 10)] * 24)
+    assert dense == 4.0 * 115200 * 115200 * 128 * 24
+    assert sta.sta_kept_flops(1, 24, 128, grid, tile, [(3, 3, 3)] * 24) == pytest.approx(dense * 27 / 300, rel=1e-12)
+    assert sta.sta_kept_flops(1, 24, 128, grid, tile, [(5, 5, 5)] * 24) == pytest.approx(dense * 125 / 300, rel=1e-12)
+    assert sta.sta_kept_flops(2, 24, 128, grid, tile, [(5, 3, 5)] * 24) == pytest.approx(2 * dense * 75 / 300, rel=1e-12)
+
+
+def test_error_returns_before_any_launch():
+    lib = sta.load_library()
+    grid, tile = I3(4, 4, 4), I3(2, 2, 2)
+    win = (ctypes.c_int * 3)(1, 1, 1)
+    fake = ctypes.c_void_p(0x10000)
+    fake2 = ctypes.c_void_p(0x90000000)
+    # NULL pointers
+    assert lib.sta_tile_permute(None, fake, 0, 0, 1, 1, 64, grid, tile, None) == 1
+    assert lib.sta_forward(None, fake, fake, fake, 1, 1, 64, grid, tile, win, 0.0, None, 0, None) == 1
+    assert lib.sta_forward(fake, fake, fake, fake2, 1, 1, 64, grid, tile, None, 0.0, None, 0, None) == 1
+    # shape: grid not a multiple of tile, non-positive dims
+    assert lib.sta_tile_permute(fake, fake2, 0, 0, 1, 1, 64, I3(5, 4, 4), tile, None) == 2
+    assert lib.sta_untile(fake, fake2, 0, 0, 0, 1, 64, grid, tile, None) == 2
+    assert lib.sta_forward(fake, fake, fake, fake2, 1, 1, 64, I3(4, 4, 3), tile, win, 0.0, None, 0, None) == 2
+    # window < 1
+    bad = (ctypes.c_int * 3)(1, 0, 1)
+    assert lib.sta_forward(fake, fake, fake, fake2, 1, 1, 64, grid, tile, bad, 0.0, None, 0, None) == 3
+    # unsupported: P = 8 not a multiple of 32; D = 48; bad dtype; D not a multiple of 8
+    assert lib.sta_forward(fake, fake, fake, fake2, 1, 1, 64, grid, tile, win, 0.0, None, 0, None) == 4
+    assert lib.sta_forward(fake, fake, fake, fake2, 1, 1, 48, I3(8, 8, 8), I3(4, 4, 2), win, 0.0, None, 0, None) == 4
+    assert lib.sta_tile_permute(fake, fake2, 2, 0, 1, 1, 64, grid, tile, None) == 4
+    assert lib.sta_tile_permute(fake, fake2, 0, 0, 1, 1, 12, grid, tile, None) == 4
+    # aliasing
+    assert lib.sta_tile_permute(fake, fake, 0, 0, 1, 1, 64, grid, tile, None) == 5
+    assert lib.sta_forward(fake, fake, fake, fake, 1, 1, 64, I3(8, 8, 8), I3(4, 4, 2), win, 0.0, None, 0, None) == 5
+    # key-tile box argument checks
+    lo, hi = I3(), I3()
+    assert lib.sta_key_tile_box(I3(2, 2, 2), I3(1, 1, 1), I3(0, 0, 2), lo, hi) == 2
+    assert lib.sta_key_tile_box(I3(2, 2, 2), I3(1, 0, 1), I3(0, 0, 1), lo, hi) == 3
+    assert sta.sta_workspace_bytes(1, 24, 128, (30, 48, 80), (6, 8, 8)) == 0

@@ -1,0 +1,265 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU
+oracle on the same seeded inputs.  Integer / byte work must be bit-exact;
+attention output must meet the tolerances in gpu_util."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_04507_amd as sta
+import synth_inputs as syn
+from oracle import sta_oracle as orc
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _as_u16(t):
+    return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+# --------------------------------------------------------------------------
+# Permutation: bit-exact
+# --------------------------------------------------------------------------
+PERM_CASES = [
+    ("C1grid", 1, 1, 64, (18, 24, 24), (6, 8, 8)),
+    ("C2grid", 1, 8, 64, (1, 64, 64), (1, 8, 8)),
+    ("C3grid", 1, 12, 128, (12, 48, 48), (6, 8, 8)),
+    ("ragged", 2, 3, 40, (6, 10, 14), (3, 5, 7)),
+    ("unit-tile", 1, 2, 8, (3, 5, 7), (1, 1, 1)),
+    ("one-tile", 1, 2, 16, (2, 3, 4), (2, 3, 4)),
+    ("wide-w", 1, 1, 128, (2, 4, 96), (1, 2, 32)),
+]
+
+
+@pytest.mark.parametrize("name,B,H,D,grid,tile", PERM_CASES)
+def test_tile_permute_and_untile_bit_exact(name, B, H, D, grid, tile):
+    N = int(np.prod(grid))
+    g = torch.Generator().manual_seed(7)
+    x = torch.randn((B, H, N, D), generator=g).to(torch.bfloat16)
+    xd = x.to(DEV)
+    y = torch.full_like(xd, float("nan"))
+    sta.sta_tile_permute(xd, y, grid, tile)
+    want = orc.tile_permute(_as_u16(x), grid, tile)
+    np.testing.assert_array_equal(_as_u16(y.cpu()), want)
+    z = torch.full_like(xd, float("nan"))
+    sta.sta_untile(y, z, grid, tile)
+    np.testing.assert_array_equal(_as_u16(z.cpu()), _as_u16(x))
+    np.testing.assert_array_equal(_as_u16(z.cpu()), orc.untile(want, grid, tile))
+
+
+def test_tile_permute_full_size_grid_bit_exact():
+    """The 30x48x80 grid at full head dim; 4 heads keep the host side light."""
+    w = syn.workload("C4")
+    N, D = w.N, w.D
+    g = torch.Generator().manual_seed(8)
+    x = torch.randn((1, 4, N, D), generator=g).to(torch.bfloat16)
+    xd = x.to(DEV)
+    y = torch.empty_like(xd)
+    sta.sta_tile_permute(xd, y, w.grid, w.tile)
+    order = torch.from_numpy(orc.tile_order(w.grid, w.tile))
+    assert torch.equal(y.cpu().view(torch.int16), x.view(torch.int16)[:, :, order, :])
+    z = torch.empty_like(xd)
+    sta.sta_untile(y, z, w.grid, w.tile)
+    assert torch.equal(z.cpu().view(torch.int16), x.view(torch.int16))
+
+
+def test_tile_permute_fused_casts_bit_exact():
+    grid, tile = (18, 24, 24), (6, 8, 8)
+    N = int(np.prod(grid))
+    g = torch.Generator().manual_seed(9)
+    x = torch.randn((1, 2, N, 64), generator=g)
+    x[0, 0, 0, :8] = torch.tensor([0.0, -0.0, float("inf"), -float("inf"), 1e-40, 3.3895e38, 1.00390625, 1.01171875])
+    xd = x.to(DEV)
+    y = torch.empty((1, 2, N, 64), dtype=torch.bfloat16, device=DEV)
+    sta.sta_tile_permute(xd, y, grid, tile)                       # f32 -> bf16, round to nearest even
+    want = orc.tile_permute(_as_u16(x.to(torch.bfloat16)), grid, tile)
+    np.testing.assert_array_equal(_as_u16(y.cpu()), want)
+    z = torch.empty((1, 2, N, 64), dtype=torch.float32, device=DEV)
+    sta.sta_untile(y, z, grid, tile)                              # bf16 -> f32, exact
+    assert torch.equal(z.cpu(), x.to(torch.bfloat16).float())
+    y32 = torch.empty_like(xd)
+    sta.sta_tile_permute(xd, y32, grid, tile)                     # f32 -> f32
+    np.testing.assert_array_equal(y32.cpu().numpy().view(np.uint32),
+                                  orc.tile_permute(x.numpy().view(np.uint32), grid, tile))
+
+
+# --------------------------------------------------------------------------
+# Key-tile lists as the device computes them: bit-exact
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("grid,tile,windows", [
+    ((30, 48, 80), (6, 8, 8), [(3, 3, 3), (1, 3, 3), (3, 3, 5), (5, 6, 10), (5, 3, 5), (5, 5, 5), (1, 1, 1)]),
+    ((12, 48, 48), (6, 8, 8), [(1, 3, 3), (2, 2, 2), (7, 1, 4)]),
+    ((1, 64, 64), (1, 8, 8), [(1, 3, 3), (1, 8, 8), (1, 5, 1), (4, 2, 9)]),
+    ((4, 4, 4), (4, 4, 4), [(1, 1, 1), (3, 3, 3)]),
+])
+def test_device_key_tile_lists_bit_exact(grid, tile, windows):
+    H = len(windows)
+    n = int(np.prod([g // t for g, t in zip(grid, tile)]))
+    counts = torch.full((H, n), -7, dtype=torch.int32, device=DEV)
+    lists = torch.full((H, n, n), -7, dtype=torch.int32, device=DEV)
+    sta.sta_dump_key_tiles(H, grid, tile, windows, counts, lists)
+    torch.cuda.synchronize()
+    for h, wt in enumerate(windows):
+        oc, ol = orc.key_tiles(grid, tile, orc.window_tiles_to_tokens(wt, tile))
+        np.testing.assert_array_equal(counts[h].cpu().numpy(), oc)
+        np.testing.assert_array_equal(lists[h].cpu().numpy(), ol)
+
+
+# --------------------------------------------------------------------------
+# Attention: whole-problem parity on the small configurations
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_attention_parity_whole_problem(name):
+    w = syn.workload(name)
+    q, k, v = syn.make_qkv(w)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    for b in range(w.B):
+        for h in range(w.H):
+            ref = gu.oracle_rows(w, q, k, v, b, h, None)
+            gu.assert_parity(out[b, h], ref, "%s b%d h%d" % (name, b, h))
+
+
+EDGE_CASES = [
+    # name, B, H, D, grid, tile, per-head windows (tiles)
+    ("p32-d64", 1, 2, 64, (4, 8, 8), (2, 4, 4), [(1, 1, 1), (3, 3, 1)]),
+    ("p96-d128", 1, 2, 128, (4, 8, 12), (4, 4, 6), [(1, 3, 3), (1, 2, 2)]),
+    ("p64-d128", 2, 2, 128, (2, 16, 16), (1, 8, 8), [(3, 1, 3), (1, 2, 1)]),
+    ("p128-d64", 1, 3, 64, (8, 8, 8), (2, 8, 8), [(3, 1, 1), (4, 1, 1), (9, 9, 9)]),
+    ("p384-d128-mixed", 2, 3, 128, (6, 16, 24), (6, 8, 8), [(1, 1, 1), (1, 3, 3), (1, 2, 3)]),
+    ("single-tile", 1, 1, 64, (6, 8, 8), (6, 8, 8), [(1, 1, 1)]),
+    ("p256-d128", 1, 1, 128, (4, 16, 16), (4, 8, 8), [(1, 3, 1)]),
+]
+
+
+@pytest.mark.parametrize("name,B,H,D,grid,tile,windows", EDGE_CASES)
+def test_attention_parity_edge_shapes(name, B, H, D, grid, tile, windows):
+    w = syn.custom(name, B, H, D, grid, tile, windows, "bf16", seed=4242)
+    q, k, v = syn.make_qkv(w)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    for b in range(B):
+        for h in range(H):
+            ref = gu.oracle_rows(w, q, k, v, b, h, None)
+            gu.assert_parity(out[b, h], ref, "%s b%d h%d" % (name, b, h))
+
+
+def test_attention_explicit_scale():
+    w = syn.custom("scale", 1, 1, 64, (2, 8, 16), (1, 8, 8), [(1, 1, 3)], "bf16", seed=5)
+    q, k, v = syn.make_qkv(w)
+    out = gu.gpu_chain(w, q, k, v, scale=0.05).float().numpy()
+    ref = gu.oracle_rows(w, q, k, v, 0, 0, None, scale=0.05)
+    gu.assert_parity(out[0, 0], ref, "scale")
+
+
+def test_full_window_equals_dense_attention_on_gpu():
+    """Window = whole grid: the STA kernel is plain softmax attention."""
+    w = syn.custom("dense", 1, 2, 128, (2, 16, 16), (1, 8, 8), [(2, 2, 2), (9, 9, 9)], "bf16", seed=6)
+    q, k, v = syn.make_qkv(w)
+    out = gu.gpu_chain(w, q, k, v).double()
+    for h in range(2):
+        s = (q[0, h].double() @ k[0, h].double().T) / np.sqrt(128.0)
+        ref = torch.softmax(s, dim=-1) @ v[0, h].double()
+        gu.assert_parity(out[0, h].numpy(), ref.numpy(), "dense h%d" % h)
+
+
+def test_kept_set_read_from_gpu_output():
+    """Q = 0 and V = one-hot(tile id): O[i, tau] = [tau kept] / kept(q tile), which reads the
+    kept set and its size straight out of the kernel's output."""
+    grid, tile = (12, 16, 16), (6, 8, 8)          # 2x2x2 = 8 tiles... widened below
+    grid, tile = (12, 24, 32), (6, 8, 8)          # 2x3x4 = 24 tiles, P = 384
+    windows = [(1, 3, 3), (3, 1, 2), (1, 1, 1), (2, 3, 4)]
+    w = syn.custom("onehot", 1, len(windows), 64, grid, tile, windows, "bf16", seed=11)
+    n = w.n_tiles
+    order = orc.tile_order(grid, tile)
+    tile_of_raster = np.empty(w.N, dtype=np.int64)
+    tile_of_raster[order] = np.repeat(np.arange(n), w.P)
+    q = torch.zeros((1, w.H, w.N, w.D), dtype=torch.bfloat16)
+    _, k, _ = syn.make_qkv(w)
+    v = torch.zeros((1, w.H, w.N, w.D), dtype=torch.bfloat16)
+    v[0, :, torch.arange(w.N), torch.from_numpy(tile_of_raster)] = 1.0
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    for h, wt in enumerate(windows):
+        counts, lists = orc.key_tiles(grid, tile, orc.window_tiles_to_tokens(wt, tile))
+        for qt in range(n):
+            rows = out[0, h, order[qt * w.P:(qt + 1) * w.P]]
+            kept = lists[qt, :counts[qt]]
+            expect = np.zeros(w.D)
+            expect[kept] = 1.0 / counts[qt]
+            mask = expect > 0
+            assert (rows[:, ~mask] == 0).all(), (h, qt)
+            np.testing.assert_allclose(rows[:, mask], np.broadcast_to(expect[mask], rows[:, mask].shape),
+                                       rtol=2.0 ** -7, atol=0)
+
+
+def test_constant_v_gives_constant_output():
+    w = syn.custom("constv", 1, 1, 128, (6, 16, 16), (6, 8, 8), [(1, 3, 3)], "bf16", seed=12)
+    q, k, _ = syn.make_qkv(w)
+    row = torch.linspace(-2, 2, 128).to(torch.bfloat16)
+    v = row.expand(1, 1, w.N, 128).contiguous()
+    out = gu.gpu_chain(w, q, k, v)
+    assert (out.float() - row.float()).abs().max().item() <= 2.0 ** -7 * 2
+
+
+# --------------------------------------------------------------------------
+# Attention: sampled parity at the larger configurations
+# --------------------------------------------------------------------------
+def test_attention_parity_c3_sampled():
+    w = syn.workload("C3")
+    q, k, v = syn.make_qkv(w)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    tiles = gu.border_and_interior_tiles(w)
+    for h in range(w.H):
+        idx = gu.stratified_query_sample(w, 128, tiles[h % len(tiles):h % len(tiles) + 1], seed=100 + h)
+        ref = gu.oracle_rows(w, q, k, v, 0, h, idx)
+        gu.assert_parity(out[0, h, idx], ref, "C3 h%d" % h)
+
+
+def _sampled_full_size(name, n_random, heads_with_full_tile, heads=None):
+    w = syn.workload(name)
+    q, k, v = syn.make_qkv(w)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    assert np.isfinite(out).all()
+    tiles = gu.border_and_interior_tiles(w)
+    stats = []
+    for h in (heads if heads is not None else range(w.H)):
+        full = [tiles[h % len(tiles)]] if h in heads_with_full_tile else []
+        idx = gu.stratified_query_sample(w, n_random, full, seed=200 + h)
+        ref = gu.oracle_rows(w, q, k, v, 0, h, idx)
+        stats.append(gu.assert_parity(out[0, h, idx], ref, "%s h%d" % (name, h)))
+    return stats
+
+
+def test_attention_parity_c4_sampled():
+    """HunyuanVideo-shaped layer, 3x3x3 window, in the launch configuration the benchmark times."""
+    _sampled_full_size("C4", n_random=32, heads_with_full_tile={0, 13})
+
+
+def test_attention_parity_c5_mixed_windows_sampled():
+    _sampled_full_size("C5", n_random=16, heads_with_full_tile=set())
+
+
+def test_attention_parity_c4_dense_sampled():
+    _sampled_full_size("C4dense", n_random=8, heads_with_full_tile=set(), heads=[0, 7, 23])
+
+
+# --------------------------------------------------------------------------
+# Error paths with real device buffers
+# --------------------------------------------------------------------------
+def test_errors_with_device_buffers():
+    x = torch.zeros((1, 1, 64, 64), dtype=torch.bfloat16, device=DEV)
+    y = torch.zeros_like(x)
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_tile_permute(x, x, (1, 8, 8), (1, 8, 8))
+    assert e.value.status == 5
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_forward(x, x, x, x, (1, 8, 8), (1, 8, 8), [(1, 1, 1)])
+    assert e.value.status == 5
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_forward(x, x, x, y, (1, 8, 8), (1, 8, 8), [(1, 0, 1)])
+    assert e.value.status == 3
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_forward(x, x, x, y, (1, 8, 8), (1, 4, 4), [(1, 1, 1)])      # P = 16
+    assert e.value.status == 4
+    torch.cuda.synchronize()
