@@ -23,6 +23,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "sta_geometry.h"
 #include "sta_internal.h"
 
@@ -250,6 +252,311 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Fast path: head dim 128, 128 queries per workgroup (4 waves x 32 queries),
+// two workgroups per CU (two waves per SIMD, so one wave's softmax overlaps the
+// other's MFMAs), K/V sub-blocks of KB keys DMA'd HBM/L2 -> LDS with
+// global_load_lds (no staging registers), double-buffered, one barrier per
+// sub-block.  LDS holds K and V row-major, 256 B per key, with the 16-byte
+// chunks of each row XOR-swizzled so that both the b128 K-operand reads and the
+// transposing ds_read_b64_tr_b16 V-operand reads are bank-conflict free:
+//   K: chunk c of row r is stored at chunk position c ^ (r & 15)
+//   V: chunk c of row r is stored at chunk position c ^ ((r & 3) << 2)
+// ---------------------------------------------------------------------------
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+#define STA_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+__device__ __forceinline__ float half_swap_max(float x)
+{
+    // v_permlane32_swap exchanges the upper half of the first operand with the lower half of the
+    // second: afterwards r[0] holds lanes 0..31 of x in both halves and r[1] lanes 32..63.
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ __forceinline__ float half_swap_sum(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// One transposing LDS read with a compile-time byte offset.
+template <int OFF>
+__device__ __forceinline__ shortx4 ds_read_tr16(uint32_t addr)
+{
+    shortx4 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+
+// Issue the 2*DB transposing reads of one 16-key group (A operands of DB PV MFMAs).
+template <int BASE, int DB, int ROWB>
+__device__ __forceinline__ void pv_issue(shortx4 (&va)[DB][2], uint32_t vaddr, const uint32_t (&v_roff)[DB])
+{
+    static_for<0, DB>([&](auto dbi) {
+        constexpr int db = decltype(dbi)::value;
+        va[db][0] = ds_read_tr16<BASE>(vaddr + v_roff[db]);
+        va[db][1] = ds_read_tr16<BASE + 8 * ROWB>(vaddr + v_roff[db]);
+    });
+}
+
+// Wait until at most PENDING LDS reads are outstanding; the operands are tied to the wait so that
+// their consumers cannot be scheduled above it.
+template <int PENDING>
+__device__ __forceinline__ void pv_wait(shortx4 (&va)[4][2])
+{
+    asm volatile("s_waitcnt lgkmcnt(%8)"
+                 : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[1][0]), "+v"(va[1][1]), "+v"(va[2][0]), "+v"(va[2][1]),
+                   "+v"(va[3][0]), "+v"(va[3][1])
+                 : "n"(PENDING));
+}
+
+template <int KB, int MINB>
+__global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw *__restrict__ q,
+                                                                 const bf16_raw *__restrict__ k,
+                                                                 const bf16_raw *__restrict__ v,
+                                                                 bf16_raw *__restrict__ o, sta::FwdParams p,
+                                                                 sta::WindowTable win, uint32_t total_items,
+                                                                 uint32_t items_per_xcd)
+{
+    constexpr int D = 128;
+    constexpr int QB = 128;
+    constexpr int MB = KB / 32;
+    constexpr int KS = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int ROWB = D * 2;                    // bytes per key row in LDS
+    constexpr int TILE_BYTES = KB * ROWB;          // one K (or V) sub-block
+    constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // K then V
+    constexpr int LOADS = TILE_BYTES / 1024 / 4;   // 1 KB DMA instructions per wave per operand
+    static_assert(KB % 32 == 0 && LOADS >= 1, "sub-block shape");
+
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_BYTES];
+
+    // ---- work item: consecutive items share K/V; hardware deals workgroups round-robin over the 8 XCDs,
+    // so give each XCD a contiguous range of items (same head, neighbouring query tiles => shared L2).
+    const uint32_t item = (blockIdx.x & 7) * items_per_xcd + (blockIdx.x >> 3);
+    if (item >= total_items) return;
+    const uint32_t qblocks_per_head = p.N / QB;
+    const uint32_t qblock = item % qblocks_per_head;
+    const uint32_t bh_local = item / qblocks_per_head;
+    const uint32_t h_local = bh_local % p.heads;
+    const uint32_t b = bh_local / p.heads;
+    const size_t bh = (size_t)b * p.H + p.head_base + h_local;
+    const uint32_t q_tile = (qblock * QB) / p.P;
+    const StaBox box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1],
+                                           win.w[h_local][2], q_tile);
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int lo = lane & 31;
+    const int hb = lane >> 5;
+
+    const bf16_raw *qh = q + (bh * p.N + (size_t)qblock * QB + (size_t)wave * 32) * D;
+    const char *kh = reinterpret_cast<const char *>(k + bh * p.N * D);
+    const char *vh = reinterpret_cast<const char *>(v + bh * p.N * D);
+
+    // ---- per-lane constants of the DMA loads: instruction i of this wave fills rows 16*wave + 4*i + (lane>>4)
+    const int ld_row0 = 16 * wave + (lane >> 4);
+    const int ld_c0 = (lane & 15) ^ (lane >> 4);                  // K: logical chunk held at this lane's LDS slot, i = 0
+    const int ld_cv = (lane & 15) ^ ((lane >> 4) << 2);           // V: same for every i
+    uint32_t k_goff[LOADS], v_goff[LOADS];
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+        k_goff[i] = (uint32_t)((ld_row0 + 4 * i) * ROWB + ((ld_c0 ^ ((4 * i) & 15)) << 4));
+        v_goff[i] = (uint32_t)((ld_row0 + 4 * i) * ROWB + (ld_cv << 4));
+    }
+    // rows 16*wave + 4*i + x with x in 0..3: (row & 15) = (4*i + x) & 15 when 16 | 16*wave, and i < 4
+    static_assert(LOADS <= 4, "swizzle shortcut assumes at most 16 rows per wave");
+
+    auto issue_loads = [&](int stage, size_t key_byte_base) {
+        char *kdst = smem + stage * STAGE_BYTES + wave * (LOADS * 1024);
+        char *vdst = kdst + TILE_BYTES;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + key_byte_base + k_goff[i]),
+                                             STA_LDS_PTR(kdst + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + key_byte_base + v_goff[i]),
+                                             STA_LDS_PTR(vdst + i * 1024), 16, 0, 0);
+        }
+    };
+
+    // ---- per-lane constants of the operand reads
+    // K (A operand of S^T = K Q^T): row 32*mb + lo, logical chunk 2*ks + hb
+    uint32_t k_roff[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) k_roff[ks] = (uint32_t)(lo * ROWB + (((2 * ks + hb) ^ (lo & 15)) << 4));
+    // V (A operand of O^T += V^T P^T) through the transposing read: within each block of 16 lanes, lane
+    // r = 4*j4 + s supplies 4 channels (4*s..4*s+3 of the block's 16) of key row j4; lane i then receives
+    // channel i of rows 0..3.
+    const int j4 = (lane & 15) >> 2, s4 = lane & 3, blk = (lane >> 4) & 1;
+    uint32_t v_roff[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+        v_roff[db] = (uint32_t)((4 * hb + j4) * ROWB + ((((db ^ j4) << 2) | (2 * blk + (s4 >> 1))) << 4) + 8 * (s4 & 1));
+
+    // ---- Q fragments (B operand of S^T), resident in registers
+    bf16x8 Qr[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        Qr[ks] = *reinterpret_cast<const bf16x8 *>(qh + (size_t)lo * D + ks * 16 + hb * 8);
+
+    floatx16 Oacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) Oacc[db][r] = 0.f;
+    float m_run = -INFINITY;      // running row max (raw scores) used as the exponent offset
+    float l_run = 0.f;            // this lane's share of the row sum
+
+    const int sub_per_tile = p.P / KB;
+    const int n_iter = box.count() * sub_per_tile;
+    int it_t = box.t.lo, it_h = box.h.lo, it_w = box.w.lo, it_s = 0;
+    auto key_byte_base = [&]() -> size_t {
+        const size_t kt = ((size_t)it_t * p.n_h + it_h) * p.n_w + it_w;
+        return (kt * p.P + (size_t)it_s * KB) * ROWB;
+    };
+    auto advance = [&]() {
+        if (++it_s == sub_per_tile) {
+            it_s = 0;
+            if (++it_w > box.w.hi) {
+                it_w = box.w.lo;
+                if (++it_h > box.h.hi) { it_h = box.h.lo; ++it_t; }
+            }
+        }
+    };
+
+    const float c = p.scale_log2e;
+    issue_loads(0, key_byte_base());
+
+    for (int iter = 0; iter < n_iter; ++iter) {
+        const int stage = iter & 1;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's DMA for sub-block `iter` has landed
+        __syncthreads();                                   // ... and everyone's; previous stage is free again
+        advance();
+        if (iter + 1 < n_iter) issue_loads(stage ^ 1, key_byte_base());
+
+        const char *kbuf = smem + stage * STAGE_BYTES;
+        const char *vbuf = kbuf + TILE_BYTES;
+
+        // ---- S^T = K Q^T ------------------------------------------------------------
+        floatx16 S[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) S[mb][r] = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kbuf + mb * 32 * ROWB + k_roff[ks]);
+                S[mb] = mfma_32x32x16(a, Qr[ks], S[mb]);
+            }
+
+        // ---- online softmax: one query column per lane ------------------------------
+        float mx = fmaxf(S[0][0], S[0][1]);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int r = (mb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(fmaxf(mx, S[mb][r]), S[mb][r + 1]);
+        mx = half_swap_max(mx);
+        // Lazy rescale: the exponent offset only moves when the max grew by more than 2^8 in the
+        // exponent, so probabilities stay below 256 and the accumulators are rarely touched.
+        const bool grow = (mx - m_run) * c > 8.0f;
+        if (__builtin_amdgcn_ballot_w64(grow)) {
+            const float m_new = grow ? mx : m_run;
+            const float alpha = exp2f((m_run - m_new) * c);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) Oacc[db][r] *= alpha;
+        }
+        const float mneg = -m_run * c;
+        bf16x8 Pb[MB][2];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(S[mb][8 * j + e], c, mneg));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(S[mb][8 * j + e + 1], c, mneg));
+                    bf16x2 pp;
+                    pp[0] = static_cast<__bf16>(p0);
+                    pp[1] = static_cast<__bf16>(p1);
+                    Pb[mb][j][e] = pp[0];
+                    Pb[mb][j][e + 1] = pp[1];
+                    bf16x2 ones;
+                    ones[0] = static_cast<__bf16>(1.0f);
+                    ones[1] = static_cast<__bf16>(1.0f);
+                    l_run = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run, false);   // sums the rounded values
+                }
+
+        // ---- O^T += V^T P^T --------------------------------------------------------
+        // The transposing reads are issued by hand (the compiler would otherwise wait for the
+        // in-flight DMA of the next sub-block before each of them) and software-pipelined one
+        // 16-key group ahead of the MFMAs that consume them.
+        const uint32_t vaddr = (uint32_t)(uintptr_t)vbuf;
+        shortx4 va[2][DB][2];
+        pv_issue<0, DB, ROWB>(va[0], vaddr, v_roff);
+        static_for<0, MB * 2>([&](auto gi) {
+            constexpr int g = decltype(gi)::value;
+            constexpr int mb = g / 2, j = g % 2;
+            if constexpr (g + 1 < MB * 2) {
+                pv_issue<(g + 1) * 16 * ROWB, DB, ROWB>(va[(g + 1) & 1], vaddr, v_roff);
+                pv_wait<DB * 2>(va[g & 1]);
+            } else {
+                pv_wait<0>(va[g & 1]);
+            }
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                typedef short shortx8 __attribute__((ext_vector_type(8)));
+                const shortx8 v01 = __builtin_shufflevector(va[g & 1][db][0], va[g & 1][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                Oacc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, v01), Pb[mb][j], Oacc[db]);
+            }
+        });
+    }
+
+    // ---- finalize -------------------------------------------------------------------
+    bf16_raw *oh = o + (bh * p.N + (size_t)qblock * QB + (size_t)wave * 32) * D;
+    const float inv = 1.f / half_swap_sum(l_run);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            bf16x4 ov;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ov[t] = static_cast<__bf16>(Oacc[db][4 * g + t] * inv);
+            *reinterpret_cast<bf16x4 *>(oh + (size_t)lo * D + db * 32 + g * 8 + hb * 4) = ov;
+        }
+}
+
+template <int KB, int MINB>
+hipError_t launch_fast_d128(const void *q, const void *k, const void *v, void *o, int B, const sta::FwdParams &p,
+                            const sta::WindowTable &win, hipStream_t stream)
+{
+    const uint32_t total = (uint32_t)B * p.heads * (p.N / 128);
+    const uint32_t per_xcd = (total + 7) / 8;
+    dim3 grid(per_xcd * 8), block(256);
+    sta_fwd_d128_kernel<KB, MINB><<<grid, block, 0, stream>>>(
+        static_cast<const bf16_raw *>(q), static_cast<const bf16_raw *>(k), static_cast<const bf16_raw *>(v),
+        static_cast<bf16_raw *>(o), p, win, total, per_xcd);
+    return hipGetLastError();
+}
+
 // Test hook: the key-tile list of every (head, query tile) from the same box function.
 __global__ void sta_dump_key_tiles_kernel(sta::FwdParams p, sta::WindowTable win, int32_t *counts, int32_t *lists)
 {
@@ -297,6 +604,8 @@ hipError_t launch_d(const void *q, const void *k, const void *v, void *o, int B,
 
 namespace sta {
 
+bool g_force_generic = false;
+
 bool forward_supported(int P, int D) { return (D == 64 || D == 128) && P > 0 && P % 32 == 0; }
 
 hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, int B, int D, const FwdParams &p,
@@ -304,6 +613,7 @@ hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, 
 {
     if (!forward_supported((int)p.P, D)) return hipErrorInvalidValue;
     if (D == 64) return launch_d<64>(q, k, v, o, B, p, win, stream);
+    if (p.P % 128 == 0 && !sta::g_force_generic) return launch_fast_d128<64, 2>(q, k, v, o, B, p, win, stream);
     return launch_d<128>(q, k, v, o, B, p, win, stream);
 }
 

@@ -43,6 +43,7 @@ struct FwdParams {
 hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, int B, int D,
                           const FwdParams &p, const WindowTable &win, hipStream_t stream);
 bool forward_supported(int P, int D);
+extern bool g_force_generic;   // debugging aid: route every shape through the generic kernel
 
 hipError_t launch_dump_key_tiles(const FwdParams &p, const WindowTable &win, int32_t *counts,
                                  int32_t *lists, hipStream_t stream);
