@@ -310,6 +310,32 @@ __device__ __forceinline__ void pv_issue(shortx4 (&va)[DB][2], uint32_t vaddr, c
     });
 }
 
+// One 16-byte LDS read with a compile-time byte offset.
+template <int OFF>
+__device__ __forceinline__ bf16x8 ds_read_b128_at(uint32_t addr)
+{
+    bf16x8 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+
+// Issue the K-operand reads of one group of 4 MFMA k-steps (A operands of S^T = K Q^T).
+template <int G, int ROWB>
+__device__ __forceinline__ void k_issue(bf16x8 (&ka)[4], uint32_t kaddr, const uint32_t (&k_roff)[8])
+{
+    constexpr int mb = G / 2, ks0 = 4 * (G % 2);
+    static_for<0, 4>([&](auto i) {
+        constexpr int ks = ks0 + decltype(i)::value;
+        ka[decltype(i)::value] = ds_read_b128_at<mb * 32 * ROWB>(kaddr + k_roff[ks]);
+    });
+}
+
+template <int PENDING>
+__device__ __forceinline__ void k_wait(bf16x8 (&ka)[4])
+{
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]) : "n"(PENDING));
+}
+
 // Wait until at most PENDING LDS reads are outstanding; the operands are tied to the wait so that
 // their consumers cannot be scheduled above it.
 template <int PENDING>
@@ -366,18 +392,19 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
     const char *kh = reinterpret_cast<const char *>(k + bh * p.N * D);
     const char *vh = reinterpret_cast<const char *>(v + bh * p.N * D);
 
-    // ---- per-lane constants of the DMA loads: instruction i of this wave fills rows 16*wave + 4*i + (lane>>4)
-    const int ld_row0 = 16 * wave + (lane >> 4);
-    const int ld_c0 = (lane & 15) ^ (lane >> 4);                  // K: logical chunk held at this lane's LDS slot, i = 0
-    const int ld_cv = (lane & 15) ^ ((lane >> 4) << 2);           // V: same for every i
+    // ---- per-lane constants of the DMA loads: each wave-wide 16 B/lane instruction fills 1 KB = 4 key rows;
+    // instruction i of this wave fills rows ROWS_PER_WAVE*wave + 4*i + (lane>>4).  A lane's LDS slot is
+    // fixed by the hardware (base + 16*lane), so the swizzle is applied on the global side: the lane
+    // fetches the logical chunk that belongs at its slot.
+    constexpr int ROWS_PER_WAVE = LOADS * 4;
     uint32_t k_goff[LOADS], v_goff[LOADS];
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-        k_goff[i] = (uint32_t)((ld_row0 + 4 * i) * ROWB + ((ld_c0 ^ ((4 * i) & 15)) << 4));
-        v_goff[i] = (uint32_t)((ld_row0 + 4 * i) * ROWB + (ld_cv << 4));
+        const int row = ROWS_PER_WAVE * wave + 4 * i + (lane >> 4);
+        const int slot = lane & 15;
+        k_goff[i] = (uint32_t)(row * ROWB + ((slot ^ (row & 15)) << 4));
+        v_goff[i] = (uint32_t)(row * ROWB + ((slot ^ ((row & 3) << 2)) << 4));
     }
-    // rows 16*wave + 4*i + x with x in 0..3: (row & 15) = (4*i + x) & 15 when 16 | 16*wave, and i < 4
-    static_assert(LOADS <= 4, "swizzle shortcut assumes at most 16 rows per wave");
 
     auto issue_loads = [&](int stage, size_t key_byte_base) {
         char *kdst = smem + stage * STAGE_BYTES + wave * (LOADS * 1024);
@@ -444,24 +471,44 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's DMA for sub-block `iter` has landed
         __syncthreads();                                   // ... and everyone's; previous stage is free again
         advance();
-        if (iter + 1 < n_iter) issue_loads(stage ^ 1, key_byte_base());
+        const bool more = iter + 1 < n_iter;
+        const size_t next_base = key_byte_base();
 
         const char *kbuf = smem + stage * STAGE_BYTES;
         const char *vbuf = kbuf + TILE_BYTES;
 
         // ---- S^T = K Q^T ------------------------------------------------------------
+        // K-operand reads are issued by hand, one group of four k-steps ahead of the MFMAs.
+        const uint32_t kaddr = (uint32_t)(uintptr_t)kbuf;
+        const uint32_t vaddr = (uint32_t)(uintptr_t)vbuf;
         floatx16 S[MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) S[mb][r] = 0.f;
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kbuf + mb * 32 * ROWB + k_roff[ks]);
-                S[mb] = mfma_32x32x16(a, Qr[ks], S[mb]);
+        bf16x8 ka[2][4];
+        k_issue<0, ROWB>(ka[0], kaddr, k_roff);
+        static_for<0, MB * 2>([&](auto gi) {
+            constexpr int g = decltype(gi)::value;
+            constexpr int mb = g / 2, ks0 = 4 * (g % 2);
+            if constexpr (g + 1 < MB * 2) {
+                k_issue<g + 1, ROWB>(ka[(g + 1) & 1], kaddr, k_roff);
+                k_wait<4>(ka[g & 1]);
+            } else {
+                k_wait<0>(ka[g & 1]);
             }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) S[mb] = mfma_32x32x16(ka[g & 1][i], Qr[ks0 + i], S[mb]);
+            // The DMA of the next sub-block is issued here, behind the first MFMA group (timing was the
+            // same with the issue placed directly after the barrier).
+            if constexpr (g == 0) {
+                if (more) issue_loads(stage ^ 1, next_base);
+            }
+            __builtin_amdgcn_sched_barrier(0);   // keep each MFMA group ahead of the next group's wait
+        });
+        // first group of V-operand reads goes out now so that its latency hides behind the softmax
+        shortx4 va[2][DB][2];
+        pv_issue<0, DB, ROWB>(va[0], vaddr, v_roff);
 
         // ---- online softmax: one query column per lane ------------------------------
         float mx = fmaxf(S[0][0], S[0][1]);
@@ -509,9 +556,6 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
         // The transposing reads are issued by hand (the compiler would otherwise wait for the
         // in-flight DMA of the next sub-block before each of them) and software-pipelined one
         // 16-key group ahead of the MFMAs that consume them.
-        const uint32_t vaddr = (uint32_t)(uintptr_t)vbuf;
-        shortx4 va[2][DB][2];
-        pv_issue<0, DB, ROWB>(va[0], vaddr, v_roff);
         static_for<0, MB * 2>([&](auto gi) {
             constexpr int g = decltype(gi)::value;
             constexpr int mb = g / 2, j = g % 2;
