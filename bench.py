@@ -30,6 +30,13 @@ import synth_inputs as syn  # noqa: E402
 BF16_MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 
+# HBM-side bytes per sta_forward launch from rocprofv3 FETCH_SIZE + WRITE_SIZE passes, each scaled by what the
+# same counter reads for a plain copy of known size (FETCH_SIZE x2.0, WRITE_SIZE x1.0 on this machine); summary in
+# profiles/sta_forward_C4_w3x3x3_pmc.txt.  Only workloads that were actually profiled have an entry.
+MEASURED_FORWARD_TRAFFIC_BYTES = {
+    ("C4", ((3, 3, 3),)): 15.33e9 + 0.708e9,
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -41,8 +48,9 @@ def parse_args():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense (full-window) comparison run")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time")
-    ap.add_argument("--profile-only", default=None, choices=[None, "forward", "permute", "layer"],
-                    help="run only this part (for rocprofv3), print nothing else")
+    ap.add_argument("--profile-only", default=None, choices=[None, "forward", "permute", "layer", "copy"],
+                    help="run only this part (for rocprofv3), print nothing else; 'copy' is a plain "
+                         "device copy of one tensor, the known-size reference for the traffic counters")
     return ap.parse_args()
 
 
@@ -144,7 +152,7 @@ def main():
 
     if args.profile_only:
         fn = {"forward": layer.forward, "permute": lambda: (layer.permute_in(), layer.untile()),
-              "layer": layer.step}[args.profile_only]
+              "layer": layer.step, "copy": lambda: layer.qt.copy_(layer.q)}[args.profile_only]
         layer.permute_in()
         for _ in range(args.warmup + args.steps):
             fn()
@@ -189,7 +197,10 @@ def main():
         "roofline": {
             "kernel": "sta_forward", "bound": "mfma",
             "achieved": fwd_tflops, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": fwd_tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+            "frac": fwd_tflops / BF16_MFMA_PEAK_TFLOPS,
+            "traffic": MEASURED_FORWARD_TRAFFIC_BYTES.get((w.name, tuple(sorted(set(w.window_tiles))))),
+            "traffic_unit": "bytes per launch (null = this workload was not profiled)",
+            "algorithmic_bytes": 4 * tensor_bytes,
         },
         "kernels": {
             "sta_forward_ms": fwd_ms, "sta_forward_tflops": fwd_tflops,
