@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0
 # same counter reads for a plain copy of known size (FETCH_SIZE x2.0, WRITE_SIZE x1.0 on this machine); summary in
 # profiles/sta_forward_C4_w3x3x3_pmc.txt.  Only workloads that were actually profiled have an entry.
 MEASURED_FORWARD_TRAFFIC_BYTES = {
-    ("C4", ((3, 3, 3),)): 15.33e9 + 0.708e9,
+    ("C4", ((3, 3, 3),)): 16.95e9 + 0.708e9,
 }
 
 
@@ -48,6 +48,9 @@ def parse_args():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense (full-window) comparison run")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line, time sta_forward for a list of uniform windows and the "
+                         "per-head mixed table on the 30x48x80 grid (speedup-versus-sparsity curve), one JSON line")
     ap.add_argument("--profile-only", default=None, choices=[None, "forward", "permute", "layer", "copy"],
                     help="run only this part (for rocprofv3), print nothing else; 'copy' is a plain "
                          "device copy of one tensor, the known-size reference for the traffic counters")
@@ -149,6 +152,30 @@ def main():
     layer = Layer(w, device)
     flops = sta.sta_kept_flops(w.B, w.H, w.D, w.grid, w.tile, w.window_tiles)
     tensor_bytes = w.B * w.H * w.N * w.D * 2
+
+    if args.sweep:
+        layer.permute_in()
+        dense_w = tuple(w.tile_grid)
+        rows = []
+        dense_ms = None
+        windows = [dense_w, (5, 5, 5), (5, 3, 5), (3, 3, 5), (3, 3, 3), (1, 3, 3), (1, 1, 1)]
+        for wt in windows:
+            table = tuple(tuple(wt) for _ in range(w.H))
+            fl = sta.sta_kept_flops(w.B, w.H, w.D, w.grid, w.tile, table)
+            ms = event_time_ms(lambda: layer.forward(table), 2 if wt == dense_w else 5, warmup=1)
+            if wt == dense_w:
+                dense_ms, dense_fl = ms, fl
+            rows.append({"window_tiles": "x".join(map(str, wt)), "kept_fraction": fl / dense_fl, "ms": ms,
+                         "tflops": fl / ms / 1e9, "frac_of_peak": fl / ms / 1e9 / BF16_MFMA_PEAK_TFLOPS,
+                         "speedup_vs_dense": dense_ms / ms, "ideal_speedup": dense_fl / fl})
+        mixed = syn.workload("C5").window_tiles
+        fl = sta.sta_kept_flops(w.B, w.H, w.D, w.grid, w.tile, mixed)
+        ms = event_time_ms(lambda: layer.forward(mixed), 3, warmup=1)
+        rows.append({"window_tiles": "C5 per-head mixed", "kept_fraction": fl / dense_fl, "ms": ms,
+                     "tflops": fl / ms / 1e9, "frac_of_peak": fl / ms / 1e9 / BF16_MFMA_PEAK_TFLOPS,
+                     "speedup_vs_dense": dense_ms / ms, "ideal_speedup": dense_fl / fl})
+        print(json.dumps({"sweep": "sta_forward on grid 30x48x80, tile 6x8x8, H=24, D=128, bf16", "rows": rows}))
+        return
 
     if args.profile_only:
         fn = {"forward": layer.forward, "permute": lambda: (layer.permute_in(), layer.untile()),

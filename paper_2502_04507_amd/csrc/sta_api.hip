@@ -103,6 +103,39 @@ void fill_window_table(sta::WindowTable *t, const int *window_tiles, int head_ba
         }
 }
 
+// Kept (query tile, key tile) pairs of one head: the box is a product of per-axis ranges, so the count factorises.
+double kept_pairs_of_head(const int n[3], const int *window3)
+{
+    double per_head = 1.0;
+    for (int a = 0; a < 3; ++a) {
+        const int w = window3[a] < 2 * n[a] ? window3[a] : 2 * n[a];
+        long sum = 0;
+        for (int qa = 0; qa < n[a]; ++qa) {
+            const StaAxisRange r = sta_axis_range(n[a], w, qa);
+            sum += r.hi - r.lo + 1;
+        }
+        per_head *= (double)sum;
+    }
+    return per_head;
+}
+
+// Heads of the launch sorted by descending cost (stable, so equal heads keep their order).
+void fill_head_order(sta::HeadOrder *o, const int *window_tiles, int head_base, int heads, const int n[3])
+{
+    double cost[sta::kMaxHeadsPerLaunch];
+    for (int h = 0; h < heads; ++h) {
+        o->h[h] = (uint16_t)h;
+        cost[h] = kept_pairs_of_head(n, window_tiles + 3 * (head_base + h));
+    }
+    for (int i = 1; i < heads; ++i) {          // insertion sort: at most 256 entries
+        const uint16_t hi = o->h[i];
+        int j = i - 1;
+        while (j >= 0 && cost[o->h[j]] < cost[hi]) { o->h[j + 1] = o->h[j]; --j; }
+        o->h[j + 1] = hi;
+    }
+    for (int h = heads; h < sta::kMaxHeadsPerLaunch; ++h) o->h[h] = 0;
+}
+
 sta::FwdParams make_fwd_params(const Shape &s, int H, float scale_log2e)
 {
     sta::FwdParams p;
@@ -165,7 +198,9 @@ int sta_forward(const void *q_tiled, const void *k_tiled, const void *v_tiled, v
         fill_window_table(&win, window_tiles, hb, heads, s.n);
         p.head_base = hb;
         p.heads = heads;
-        hipError_t e = sta::launch_forward(q_tiled, k_tiled, v_tiled, o_tiled, B, D, p, win,
+        sta::HeadOrder order;
+        fill_head_order(&order, window_tiles, hb, heads, s.n);
+        hipError_t e = sta::launch_forward(q_tiled, k_tiled, v_tiled, o_tiled, B, D, p, win, order,
                                            static_cast<hipStream_t>(hip_stream));
         if (e != hipSuccess) return STA_ERR_HIP;
     }
@@ -227,21 +262,7 @@ double sta_kept_flops(int B, int H, int D, const int grid[3], const int tile[3],
     if (check_shape(B, H, D, grid, tile, &s) != STA_OK) return 0.0;
     if (check_windows(H, window_tiles) != STA_OK) return 0.0;
     double pairs = 0.0;
-    for (int h = 0; h < H; ++h) {
-        // the box is a product of per-axis ranges, so the pair count factorises
-        double per_head = 1.0;
-        for (int a = 0; a < 3; ++a) {
-            const int n = s.n[a];
-            const int w = window_tiles[3 * h + a] < 2 * n ? window_tiles[3 * h + a] : 2 * n;
-            long sum = 0;
-            for (int qa = 0; qa < n; ++qa) {
-                const StaAxisRange r = sta_axis_range(n, w, qa);
-                sum += r.hi - r.lo + 1;
-            }
-            per_head *= (double)sum;
-        }
-        pairs += per_head;
-    }
+    for (int h = 0; h < H; ++h) pairs += kept_pairs_of_head(s.n, window_tiles + 3 * h);
     return 4.0 * (double)s.P * (double)s.P * (double)D * pairs * (double)B;
 }
 

@@ -352,8 +352,8 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
                                                                  const bf16_raw *__restrict__ k,
                                                                  const bf16_raw *__restrict__ v,
                                                                  bf16_raw *__restrict__ o, sta::FwdParams p,
-                                                                 sta::WindowTable win, uint32_t total_items,
-                                                                 uint32_t items_per_xcd)
+                                                                 sta::WindowTable win, sta::HeadOrder order,
+                                                                 uint32_t n_bh)
 {
     constexpr int D = 128;
     constexpr int QB = 128;
@@ -368,15 +368,25 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
 
     __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_BYTES];
 
-    // ---- work item: consecutive items share K/V; hardware deals workgroups round-robin over the 8 XCDs,
-    // so give each XCD a contiguous range of items (same head, neighbouring query tiles => shared L2).
-    const uint32_t item = (blockIdx.x & 7) * items_per_xcd + (blockIdx.x >> 3);
-    if (item >= total_items) return;
+    // ---- work item.  The hardware deals workgroup ids round-robin over the 8 XCDs (each with its own L2) and,
+    // inside an XCD, starts them in increasing order.  Every (batch, head) slice is cut into 8 contiguous
+    // ranges of query blocks, one per XCD, so each XCD carries one eighth of every head whatever the per-head
+    // windows are (load balance: with mixed per-head windows this halved the launch time), and its resident
+    // workgroups are neighbouring query blocks of one head (shared K/V in L2).  Heads are visited in
+    // descending cost order, so the tail of the launch is made of cheap items.  The price is that
+    // neighbouring ranges of a head fetch the same border K/V tiles into two L2s: measured HBM-side reads
+    // rose by about 10 % against giving each XCD whole heads.
+    const uint32_t xcd = blockIdx.x & 7;
+    const uint32_t slot = blockIdx.x >> 3;
     const uint32_t qblocks_per_head = p.N / QB;
-    const uint32_t qblock = item % qblocks_per_head;
-    const uint32_t bh_local = item / qblocks_per_head;
-    const uint32_t h_local = bh_local % p.heads;
-    const uint32_t b = bh_local / p.heads;
+    const uint32_t seg_lo = (xcd * qblocks_per_head) >> 3;
+    const uint32_t seg_len = (((xcd + 1) * qblocks_per_head) >> 3) - seg_lo;
+    if (seg_len == 0) return;
+    const uint32_t bh_rank = slot / seg_len;
+    if (bh_rank >= n_bh) return;
+    const uint32_t qblock = seg_lo + (slot - bh_rank * seg_len);
+    const uint32_t h_local = order.h[bh_rank / (n_bh / p.heads)];     // batch entries of one head are adjacent
+    const uint32_t b = bh_rank % (n_bh / p.heads);
     const size_t bh = (size_t)b * p.H + p.head_base + h_local;
     const uint32_t q_tile = (qblock * QB) / p.P;
     const StaBox box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1],
@@ -590,14 +600,15 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
 
 template <int KB, int MINB>
 hipError_t launch_fast_d128(const void *q, const void *k, const void *v, void *o, int B, const sta::FwdParams &p,
-                            const sta::WindowTable &win, hipStream_t stream)
+                            const sta::WindowTable &win, const sta::HeadOrder &order, hipStream_t stream)
 {
-    const uint32_t total = (uint32_t)B * p.heads * (p.N / 128);
-    const uint32_t per_xcd = (total + 7) / 8;
-    dim3 grid(per_xcd * 8), block(256);
+    const uint32_t qblocks_per_head = p.N / 128;
+    const uint32_t max_seg = (qblocks_per_head + 7) / 8;          // longest of the 8 per-XCD ranges
+    const uint32_t n_bh = (uint32_t)B * p.heads;
+    dim3 grid(8 * max_seg * n_bh), block(256);
     sta_fwd_d128_kernel<KB, MINB><<<grid, block, 0, stream>>>(
         static_cast<const bf16_raw *>(q), static_cast<const bf16_raw *>(k), static_cast<const bf16_raw *>(v),
-        static_cast<bf16_raw *>(o), p, win, total, per_xcd);
+        static_cast<bf16_raw *>(o), p, win, order, n_bh);
     return hipGetLastError();
 }
 
@@ -653,11 +664,11 @@ bool g_force_generic = false;
 bool forward_supported(int P, int D) { return (D == 64 || D == 128) && P > 0 && P % 32 == 0; }
 
 hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, int B, int D, const FwdParams &p,
-                          const WindowTable &win, hipStream_t stream)
+                          const WindowTable &win, const HeadOrder &order, hipStream_t stream)
 {
     if (!forward_supported((int)p.P, D)) return hipErrorInvalidValue;
     if (D == 64) return launch_d<64>(q, k, v, o, B, p, win, stream);
-    if (p.P % 128 == 0 && !sta::g_force_generic) return launch_fast_d128<64, 2>(q, k, v, o, B, p, win, stream);
+    if (p.P % 128 == 0 && !sta::g_force_generic) return launch_fast_d128<64, 2>(q, k, v, o, B, p, win, order, stream);
     return launch_d<128>(q, k, v, o, B, p, win, stream);
 }
 

@@ -28,6 +28,11 @@ struct WindowTable {
     uint16_t w[kMaxHeadsPerLaunch][3];   // window in tiles per head of this launch (clamped to 2*n)
 };
 
+// Heads of one launch in the order the kernel visits them (most expensive first).
+struct HeadOrder {
+    uint16_t h[kMaxHeadsPerLaunch];
+};
+
 struct FwdParams {
     uint32_t N;            // tokens per head
     uint32_t P;            // tokens per tile
@@ -41,7 +46,8 @@ struct FwdParams {
 
 // Returns hipErrorInvalidValue if no kernel instance exists for (P, D).
 hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, int B, int D,
-                          const FwdParams &p, const WindowTable &win, hipStream_t stream);
+                          const FwdParams &p, const WindowTable &win, const HeadOrder &order,
+                          hipStream_t stream);
 bool forward_supported(int P, int D);
 extern bool g_force_generic;   // debugging aid: route every shape through the generic kernel
 
