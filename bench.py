@@ -201,9 +201,11 @@ def main():
     fwd_ms = event_time_ms(layer.forward, iters)
     perm_ms = event_time_ms(lambda: sta.sta_tile_permute(layer.q, layer.qt, w.grid, w.tile), iters)
     untile_ms = event_time_ms(layer.untile, iters)
+    copy_ms = event_time_ms(lambda: layer.qt.copy_(layer.q), iters)      # plain device copy of the same tensor
     fwd_tflops = flops / (fwd_ms * 1e-3) / 1e12
     perm_gbs = 2.0 * tensor_bytes / (perm_ms * 1e-3) / 1e9
     untile_gbs = 2.0 * tensor_bytes / (untile_ms * 1e-3) / 1e9
+    copy_gbs = 2.0 * tensor_bytes / (copy_ms * 1e-3) / 1e9
 
     out = {
         "metric": "STA fwd effective TFLOP/s (kept tiles) + ms/layer at 115,200 tokens, d=128",
@@ -235,6 +237,9 @@ def main():
             "sta_tile_permute_frac_hbm": perm_gbs / HBM_PEAK_GBS,
             "sta_untile_ms": untile_ms, "sta_untile_GBs": untile_gbs,
             "sta_untile_frac_hbm": untile_gbs / HBM_PEAK_GBS,
+            "plain_copy_ms": copy_ms, "plain_copy_GBs": copy_gbs,
+            "sta_tile_permute_frac_of_plain_copy": perm_gbs / copy_gbs,
+            "sta_untile_frac_of_plain_copy": untile_gbs / copy_gbs,
         },
         "paper_context": "H100 bf16, same shape: STA w=(18,24,24) 25.38 ms, MFU 58.79%; dense FA3 265.28 ms "
                          "(paper Table 2; other hardware, context only)",

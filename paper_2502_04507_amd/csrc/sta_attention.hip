@@ -23,23 +23,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <type_traits>
-
+#include "sta_device_util.h"
 #include "sta_geometry.h"
 #include "sta_internal.h"
 
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef uint16_t bf16_raw;
-
-__device__ __forceinline__ floatx16 mfma_32x32x16(bf16x8 a, bf16x8 b, floatx16 c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
 
 // Position inside a group of 16 keys at which key `k16` (0..15) is stored in the
 // transposed V buffer: the accumulator of S^T holds, for half hb, keys
@@ -264,89 +252,6 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
 //   K: chunk c of row r is stored at chunk position c ^ (r & 15)
 //   V: chunk c of row r is stored at chunk position c ^ ((r & 3) << 2)
 // ---------------------------------------------------------------------------
-typedef short shortx4 __attribute__((ext_vector_type(4)));
-#define STA_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
-
-__device__ __forceinline__ float half_swap_max(float x)
-{
-    // v_permlane32_swap exchanges the upper half of the first operand with the lower half of the
-    // second: afterwards r[0] holds lanes 0..31 of x in both halves and r[1] lanes 32..63.
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-
-__device__ __forceinline__ float half_swap_sum(float x)
-{
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
-// One transposing LDS read with a compile-time byte offset.
-template <int OFF>
-__device__ __forceinline__ shortx4 ds_read_tr16(uint32_t addr)
-{
-    shortx4 r;
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-    return r;
-}
-
-// Issue the 2*DB transposing reads of one 16-key group (A operands of DB PV MFMAs).
-template <int BASE, int DB, int ROWB>
-__device__ __forceinline__ void pv_issue(shortx4 (&va)[DB][2], uint32_t vaddr, const uint32_t (&v_roff)[DB])
-{
-    static_for<0, DB>([&](auto dbi) {
-        constexpr int db = decltype(dbi)::value;
-        va[db][0] = ds_read_tr16<BASE>(vaddr + v_roff[db]);
-        va[db][1] = ds_read_tr16<BASE + 8 * ROWB>(vaddr + v_roff[db]);
-    });
-}
-
-// One 16-byte LDS read with a compile-time byte offset.
-template <int OFF>
-__device__ __forceinline__ bf16x8 ds_read_b128_at(uint32_t addr)
-{
-    bf16x8 r;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-    return r;
-}
-
-// Issue the K-operand reads of one group of 4 MFMA k-steps (A operands of S^T = K Q^T).
-template <int G, int ROWB>
-__device__ __forceinline__ void k_issue(bf16x8 (&ka)[4], uint32_t kaddr, const uint32_t (&k_roff)[8])
-{
-    constexpr int mb = G / 2, ks0 = 4 * (G % 2);
-    static_for<0, 4>([&](auto i) {
-        constexpr int ks = ks0 + decltype(i)::value;
-        ka[decltype(i)::value] = ds_read_b128_at<mb * 32 * ROWB>(kaddr + k_roff[ks]);
-    });
-}
-
-template <int PENDING>
-__device__ __forceinline__ void k_wait(bf16x8 (&ka)[4])
-{
-    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]) : "n"(PENDING));
-}
-
-// Wait until at most PENDING LDS reads are outstanding; the operands are tied to the wait so that
-// their consumers cannot be scheduled above it.
-template <int PENDING>
-__device__ __forceinline__ void pv_wait(shortx4 (&va)[4][2])
-{
-    asm volatile("s_waitcnt lgkmcnt(%8)"
-                 : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[1][0]), "+v"(va[1][1]), "+v"(va[2][0]), "+v"(va[2][1]),
-                   "+v"(va[3][0]), "+v"(va[3][1])
-                 : "n"(PENDING));
-}
-
 template <int KB, int MINB>
 __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw *__restrict__ q,
                                                                  const bf16_raw *__restrict__ k,
