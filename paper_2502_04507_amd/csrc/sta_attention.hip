@@ -252,8 +252,8 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
 //   K: chunk c of row r is stored at chunk position c ^ (r & 15)
 //   V: chunk c of row r is stored at chunk position c ^ ((r & 3) << 2)
 // ---------------------------------------------------------------------------
-template <int KB, int MINB>
-__global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw *__restrict__ q,
+template <int NW, int KB, int STAGES, int MINB>
+__global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_raw *__restrict__ q,
                                                                  const bf16_raw *__restrict__ k,
                                                                  const bf16_raw *__restrict__ v,
                                                                  bf16_raw *__restrict__ o, sta::FwdParams p,
@@ -261,17 +261,20 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
                                                                  uint32_t n_bh)
 {
     constexpr int D = 128;
-    constexpr int QB = 128;
+    constexpr int QB = NW * 32;                    // queries per workgroup: one 32-query block per wave
     constexpr int MB = KB / 32;
     constexpr int KS = D / 16;
     constexpr int DB = D / 32;
     constexpr int ROWB = D * 2;                    // bytes per key row in LDS
     constexpr int TILE_BYTES = KB * ROWB;          // one K (or V) sub-block
     constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // K then V
-    constexpr int LOADS = TILE_BYTES / 1024 / 4;   // 1 KB DMA instructions per wave per operand
-    static_assert(KB % 32 == 0 && LOADS >= 1, "sub-block shape");
+    constexpr int INSTR = TILE_BYTES / 1024;       // 1 KB DMA instructions per operand per sub-block
+    constexpr int LOADS = INSTR / NW > 0 ? INSTR / NW : 1;   // ... issued by each loading wave
+    constexpr int LOADERS = INSTR / LOADS;         // waves 0 .. LOADERS-1 issue the DMA
+    static_assert(KB % 32 == 0 && INSTR % LOADS == 0 && LOADERS <= NW, "sub-block shape");
+    static_assert(STAGES >= 2 && STAGES <= 4, "LDS stages");
 
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_BYTES];
 
     // ---- work item.  The hardware deals workgroup ids round-robin over the 8 XCDs (each with its own L2) and,
     // inside an XCD, starts them in increasing order.  Every (batch, head) slice is cut into 8 contiguous
@@ -322,7 +325,7 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
     }
 
     auto issue_loads = [&](int stage, size_t key_byte_base) {
-        char *kdst = smem + stage * STAGE_BYTES + wave * (LOADS * 1024);
+        char *kdst = smem + stage * STAGE_BYTES + wave * (LOADS * 1024);   // only waves < LOADERS get here
         char *vdst = kdst + TILE_BYTES;
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
@@ -379,15 +382,30 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
     };
 
     const float c = p.scale_log2e;
-    issue_loads(0, key_byte_base());
+
+    // ---- pipeline: up to STAGES-1 sub-blocks are in flight.  (it_t, it_h, it_w, it_s) always names the next
+    // sub-block to request; `issued` counts the requests made so far.
+    int issued = 0;
+    auto issue_next = [&]() {
+        if (issued < n_iter) {
+            if (wave < LOADERS) issue_loads(issued % STAGES, key_byte_base());
+            advance();
+            ++issued;
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue_next();
 
     for (int iter = 0; iter < n_iter; ++iter) {
-        const int stage = iter & 1;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's DMA for sub-block `iter` has landed
-        __syncthreads();                                   // ... and everyone's; previous stage is free again
-        advance();
-        const bool more = iter + 1 < n_iter;
-        const size_t next_base = key_byte_base();
+        const int stage = iter % STAGES;
+        // This wave's DMA for sub-block `iter` must have landed; the requests for later sub-blocks (2*LOADS
+        // instructions each, returned in order) may stay outstanding.
+        const int pend = issued - 1 - iter;
+        if (STAGES <= 2 || pend == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (STAGES <= 3 || pend == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * LOADS) : "memory");
+        __syncthreads();   // ... and everyone's; the stage read in the previous iteration is free again
+        issue_next();      // refills stage (iter - 1) % STAGES
 
         const char *kbuf = smem + stage * STAGE_BYTES;
         const char *vbuf = kbuf + TILE_BYTES;
@@ -414,11 +432,6 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) S[mb] = mfma_32x32x16(ka[g & 1][i], Qr[ks0 + i], S[mb]);
-            // The DMA of the next sub-block is issued here, behind the first MFMA group (timing was the
-            // same with the issue placed directly after the barrier).
-            if constexpr (g == 0) {
-                if (more) issue_loads(stage ^ 1, next_base);
-            }
             __builtin_amdgcn_sched_barrier(0);   // keep each MFMA group ahead of the next group's wait
         });
         // first group of V-operand reads goes out now so that its latency hides behind the softmax
@@ -503,15 +516,15 @@ __global__ __launch_bounds__(256, MINB) void sta_fwd_d128_kernel(const bf16_raw 
         }
 }
 
-template <int KB, int MINB>
+template <int NW, int KB, int STAGES, int MINB>
 hipError_t launch_fast_d128(const void *q, const void *k, const void *v, void *o, int B, const sta::FwdParams &p,
                             const sta::WindowTable &win, const sta::HeadOrder &order, hipStream_t stream)
 {
-    const uint32_t qblocks_per_head = p.N / 128;
+    const uint32_t qblocks_per_head = p.N / (NW * 32);
     const uint32_t max_seg = (qblocks_per_head + 7) / 8;          // longest of the 8 per-XCD ranges
     const uint32_t n_bh = (uint32_t)B * p.heads;
-    dim3 grid(8 * max_seg * n_bh), block(256);
-    sta_fwd_d128_kernel<KB, MINB><<<grid, block, 0, stream>>>(
+    dim3 grid(8 * max_seg * n_bh), block(NW * 64);
+    sta_fwd_d128_kernel<NW, KB, STAGES, MINB><<<grid, block, 0, stream>>>(
         static_cast<const bf16_raw *>(q), static_cast<const bf16_raw *>(k), static_cast<const bf16_raw *>(v),
         static_cast<bf16_raw *>(o), p, win, order, n_bh);
     return hipGetLastError();
@@ -573,7 +586,12 @@ hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, 
 {
     if (!forward_supported((int)p.P, D)) return hipErrorInvalidValue;
     if (D == 64) return launch_d<64>(q, k, v, o, B, p, win, stream);
-    if (p.P % 128 == 0 && !sta::g_force_generic) return launch_fast_d128<64, 2>(q, k, v, o, B, p, win, order, stream);
+    // A tile of 384 tokens (the paper's 6x8x8) gets one 12-wave workgroup per query tile: every K/V sub-block
+    // fetched from L2 then serves 384 queries instead of 128.  Measured at the 115,200-token layer, window
+    // 3x3x3: 12.8-13.1 ms against 13.6-13.7 ms for the 4-wave shape in the same session; 2 LDS stages were
+    // faster than 3 (13.15 ms) or 4 (13.3 ms).
+    if (p.P % 384 == 0 && !sta::g_force_generic) return launch_fast_d128<12, 32, 2, 1>(q, k, v, o, B, p, win, order, stream);
+    if (p.P % 128 == 0 && !sta::g_force_generic) return launch_fast_d128<4, 64, 2, 2>(q, k, v, o, B, p, win, order, stream);
     return launch_d<128>(q, k, v, o, B, p, win, stream);
 }
 
