@@ -145,6 +145,59 @@ def test_attention_parity_edge_shapes(name, B, H, D, grid, tile, windows):
             gu.assert_parity(out[b, h], ref, "%s b%d h%d" % (name, b, h))
 
 
+def test_attention_many_heads_chunked_launch():
+    """More heads than one launch carries in its argument table (256): heads go out in chunks,
+    each with its own window; every head must come back right."""
+    H = 260
+    windows = [((h % 3) + 1, 1, (h % 2) * 2 + 1) for h in range(H)]
+    w = syn.custom("manyheads", 1, H, 128, (2, 8, 32), (1, 8, 16), windows, "bf16", seed=77)   # P = 128, 2x1x2 tiles
+    q, k, v = syn.make_qkv(w)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    for h in list(range(0, H, 37)) + [255, 256, 257, 259]:
+        ref = gu.oracle_rows(w, q, k, v, 0, h, None)
+        gu.assert_parity(out[0, h], ref, "manyheads h%d" % h)
+
+
+def test_attention_tile_of_768_tokens():
+    """P = 768: two 384-query workgroups share one query tile and must use the same key-tile box."""
+    w = syn.custom("p768", 1, 2, 128, (12, 16, 16), (12, 8, 8), [(1, 1, 2), (1, 2, 1)], "bf16", seed=78)
+    q, k, v = syn.make_qkv(w)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    for h in range(2):
+        ref = gu.oracle_rows(w, q, k, v, 0, h, None)
+        gu.assert_parity(out[0, h], ref, "p768 h%d" % h)
+
+
+@pytest.mark.parametrize("tile,grid", [((6, 8, 8), (6, 16, 24)), ((2, 8, 8), (4, 16, 16))])
+def test_attention_running_max_keeps_growing(tile, grid):
+    """Keys are scaled so that the row maximum rises from sub-block to sub-block and from tile to tile
+    (and large query norms make the steps big): the rescale path of the online softmax is taken many
+    times, late in the loop, not only on the first block.  Both kernel shapes (384- and 128-token tiles)."""
+    w = syn.custom("growmax", 1, 2, 128, grid, tile, [(1, 3, 3), (3, 3, 3)], "bf16", seed=79)
+    q, k, v = syn.make_qkv(w)
+    order = torch.from_numpy(orc.tile_order(w.grid, w.tile))
+    ramp_tiled = torch.linspace(0.2, 6.0, w.N)                      # grows along the TILED sequence
+    ramp = torch.empty(w.N)
+    ramp[order] = ramp_tiled
+    k = (k.float() * ramp[None, None, :, None]).to(torch.bfloat16)
+    q = (q.float() * 2.0).to(torch.bfloat16)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    for h in range(2):
+        ref = gu.oracle_rows(w, q, k, v, 0, h, None)
+        gu.assert_parity(out[0, h], ref, "growmax h%d" % h)
+
+
+def test_attention_large_scores_stay_finite():
+    """Scores of a few hundred before scaling: exponent offsets must keep everything finite."""
+    w = syn.custom("bigscores", 1, 1, 128, (6, 8, 16), (6, 8, 8), [(1, 1, 3)], "bf16", seed=80)
+    q, k, v = syn.make_qkv(w)
+    q = (q.float() * 6.0).to(torch.bfloat16)
+    k = (k.float() * 6.0).to(torch.bfloat16)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    ref = gu.oracle_rows(w, q, k, v, 0, 0, None)
+    gu.assert_parity(out[0, 0], ref, "bigscores")
+
+
 def test_attention_explicit_scale():
     w = syn.custom("scale", 1, 1, 64, (2, 8, 16), (1, 8, 8), [(1, 1, 3)], "bf16", seed=5)
     q, k, v = syn.make_qkv(w)
