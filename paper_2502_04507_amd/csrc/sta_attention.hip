@@ -367,16 +367,21 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     const int sub_per_tile = p.P / KB;
     const int n_iter = box.count() * sub_per_tile;
     int it_t = box.t.lo, it_h = box.h.lo, it_w = box.w.lo, it_s = 0;
-    auto key_byte_base = [&]() -> size_t {
+    auto row_start = [&]() -> size_t {      // byte offset of key tile (it_t, it_h, it_w) inside the head
         const size_t kt = ((size_t)it_t * p.n_h + it_h) * p.n_w + it_w;
-        return (kt * p.P + (size_t)it_s * KB) * ROWB;
+        return kt * p.P * ROWB;
     };
+    // Key tiles that are neighbours along w are neighbours in memory, so the offset simply keeps growing by one
+    // sub-block until the walk wraps to the next row of the box.
+    size_t next_base = row_start();
     auto advance = [&]() {
+        next_base += (size_t)KB * ROWB;
         if (++it_s == sub_per_tile) {
             it_s = 0;
             if (++it_w > box.w.hi) {
                 it_w = box.w.lo;
                 if (++it_h > box.h.hi) { it_h = box.h.lo; ++it_t; }
+                next_base = row_start();
             }
         }
     };
@@ -388,7 +393,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     int issued = 0;
     auto issue_next = [&]() {
         if (issued < n_iter) {
-            if (wave < LOADERS) issue_loads(issued % STAGES, key_byte_base());
+            if (wave < LOADERS) issue_loads(issued % STAGES, next_base);
             advance();
             ++issued;
         }
