@@ -338,17 +338,18 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
 
     // ---- per-lane constants of the operand reads
     // K (A operand of S^T = K Q^T): row 32*mb + lo, logical chunk 2*ks + hb
-    uint32_t k_roff[KS];
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
+    uint32_t k_addr[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) k_roff[ks] = (uint32_t)(lo * ROWB + (((2 * ks + hb) ^ (lo & 15)) << 4));
+    for (int ks = 0; ks < KS; ++ks) k_addr[ks] = smem_addr + (uint32_t)(lo * ROWB + (((2 * ks + hb) ^ (lo & 15)) << 4));
     // V (A operand of O^T += V^T P^T) through the transposing read: within each block of 16 lanes, lane
     // r = 4*j4 + s supplies 4 channels (4*s..4*s+3 of the block's 16) of key row j4; lane i then receives
     // channel i of rows 0..3.
     const int j4 = (lane & 15) >> 2, s4 = lane & 3, blk = (lane >> 4) & 1;
-    uint32_t v_roff[DB];
+    uint32_t v_addr[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
-        v_roff[db] = (uint32_t)((4 * hb + j4) * ROWB + ((((db ^ j4) << 2) | (2 * blk + (s4 >> 1))) << 4) + 8 * (s4 & 1));
+        v_addr[db] = smem_addr + (uint32_t)((4 * hb + j4) * ROWB + ((((db ^ j4) << 2) | (2 * blk + (s4 >> 1))) << 4) + 8 * (s4 & 1));
 
     // ---- Q fragments (B operand of S^T), resident in registers
     bf16x8 Qr[KS];
@@ -401,8 +402,12 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s) issue_next();
 
-    for (int iter = 0; iter < n_iter; ++iter) {
-        const int stage = iter % STAGES;
+    // One sub-block.  The LDS stage is a compile-time constant here (the loop below is unrolled over the
+    // stages), so every operand read carries its stage as an immediate offset and needs no address arithmetic.
+    auto sub_block = [&](auto stage_c, int iter) {
+        constexpr int stage = decltype(stage_c)::value;
+        constexpr int KOFF = stage * STAGE_BYTES;
+        constexpr int VOFF = KOFF + TILE_BYTES;
         // This wave's DMA for sub-block `iter` must have landed; the requests for later sub-blocks (2*LOADS
         // instructions each, returned in order) may stay outstanding.
         const int pend = issued - 1 - iter;
@@ -412,25 +417,20 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
         __syncthreads();   // ... and everyone's; the stage read in the previous iteration is free again
         issue_next();      // refills stage (iter - 1) % STAGES
 
-        const char *kbuf = smem + stage * STAGE_BYTES;
-        const char *vbuf = kbuf + TILE_BYTES;
-
         // ---- S^T = K Q^T ------------------------------------------------------------
         // K-operand reads are issued by hand, one group of four k-steps ahead of the MFMAs.
-        const uint32_t kaddr = (uint32_t)(uintptr_t)kbuf;
-        const uint32_t vaddr = (uint32_t)(uintptr_t)vbuf;
         floatx16 S[MB];
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) S[mb][r] = 0.f;
         bf16x8 ka[2][4];
-        k_issue<0, ROWB>(ka[0], kaddr, k_roff);
+        k_issue<0, ROWB, KOFF>(ka[0], k_addr);
         static_for<0, MB * 2>([&](auto gi) {
             constexpr int g = decltype(gi)::value;
             constexpr int mb = g / 2, ks0 = 4 * (g % 2);
             if constexpr (g + 1 < MB * 2) {
-                k_issue<g + 1, ROWB>(ka[(g + 1) & 1], kaddr, k_roff);
+                k_issue<g + 1, ROWB, KOFF>(ka[(g + 1) & 1], k_addr);
                 k_wait<4>(ka[g & 1]);
             } else {
                 k_wait<0>(ka[g & 1]);
@@ -441,14 +441,16 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
         });
         // first group of V-operand reads goes out now so that its latency hides behind the softmax
         shortx4 va[2][DB][2];
-        pv_issue<0, DB, ROWB>(va[0], vaddr, v_roff);
+        pv_issue<VOFF, DB, ROWB>(va[0], v_addr);
 
         // ---- online softmax: one query column per lane ------------------------------
-        float mx = fmaxf(S[0][0], S[0][1]);
+        float mx = max3(S[0][0], S[0][1], S[0][2]);
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
+        for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-            for (int r = (mb == 0 ? 2 : 0); r < 16; r += 2) mx = fmaxf(fmaxf(mx, S[mb][r]), S[mb][r + 1]);
+            for (int r = (mb == 0 ? 3 : 1); r + 1 < 16; r += 2) mx = max3(mx, S[mb][r], S[mb][r + 1]);
+            mx = max3(mx, S[mb][15], mb == 0 ? S[mb][15] : S[mb][0]);
+        }
         mx = half_swap_max(mx);
         // Lazy rescale: the exponent offset only moves when the max grew by more than 2^8 in the
         // exponent, so probabilities stay below 256 and the accumulators are rarely touched.
@@ -493,7 +495,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
             constexpr int g = decltype(gi)::value;
             constexpr int mb = g / 2, j = g % 2;
             if constexpr (g + 1 < MB * 2) {
-                pv_issue<(g + 1) * 16 * ROWB, DB, ROWB>(va[(g + 1) & 1], vaddr, v_roff);
+                pv_issue<VOFF + (g + 1) * 16 * ROWB, DB, ROWB>(va[(g + 1) & 1], v_addr);
                 pv_wait<DB * 2>(va[g & 1]);
             } else {
                 pv_wait<0>(va[g & 1]);
@@ -504,6 +506,12 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
                 const shortx8 v01 = __builtin_shufflevector(va[g & 1][db][0], va[g & 1][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
                 Oacc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, v01), Pb[mb][j], Oacc[db]);
             }
+        });
+    };
+
+    for (int iter = 0; iter < n_iter; iter += STAGES) {
+        static_for<0, STAGES>([&](auto st) {
+            if (iter + decltype(st)::value < n_iter) sub_block(st, iter + decltype(st)::value);
         });
     }
 

@@ -22,12 +22,21 @@ __device__ __forceinline__ floatx16 mfma_32x32x16(bf16x8 a, bf16x8 b, floatx16 c
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 #define STA_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
+// max(a, b, c) in one instruction (the compiler would add a canonicalising max per MFMA result first).
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 __device__ __forceinline__ float half_swap_max(float x)
 {
     // v_permlane32_swap exchanges the upper half of the first operand with the lower half of the
     // second: afterwards r[0] holds lanes 0..31 of x in both halves and r[1] lanes 32..63.
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    const float a = __uint_as_float(r[0]), b = __uint_as_float(r[1]);
+    return max3(a, b, b);
 }
 
 __device__ __forceinline__ float half_swap_sum(float x)
@@ -56,12 +65,12 @@ __device__ __forceinline__ shortx4 ds_read_tr16(uint32_t addr)
 
 // Issue the 2*DB transposing reads of one 16-key group (A operands of DB PV MFMAs).
 template <int BASE, int DB, int ROWB>
-__device__ __forceinline__ void pv_issue(shortx4 (&va)[DB][2], uint32_t vaddr, const uint32_t (&v_roff)[DB])
+__device__ __forceinline__ void pv_issue(shortx4 (&va)[DB][2], const uint32_t (&v_addr)[DB])
 {
     static_for<0, DB>([&](auto dbi) {
         constexpr int db = decltype(dbi)::value;
-        va[db][0] = ds_read_tr16<BASE>(vaddr + v_roff[db]);
-        va[db][1] = ds_read_tr16<BASE + 8 * ROWB>(vaddr + v_roff[db]);
+        va[db][0] = ds_read_tr16<BASE>(v_addr[db]);
+        va[db][1] = ds_read_tr16<BASE + 8 * ROWB>(v_addr[db]);
     });
 }
 
@@ -75,13 +84,15 @@ __device__ __forceinline__ bf16x8 ds_read_b128_at(uint32_t addr)
 }
 
 // Issue the K-operand reads of one group of 4 MFMA k-steps (A operands of S^T = K Q^T).
-template <int G, int ROWB>
-__device__ __forceinline__ void k_issue(bf16x8 (&ka)[4], uint32_t kaddr, const uint32_t (&k_roff)[8])
+// k_addr[ks] is the lane's LDS address of its chunk for k-step ks in stage 0, row block 0; BASE (a compile-time
+// byte offset, e.g. the stage) goes into the instruction's immediate.
+template <int G, int ROWB, int BASE>
+__device__ __forceinline__ void k_issue(bf16x8 (&ka)[4], const uint32_t (&k_addr)[8])
 {
     constexpr int mb = G / 2, ks0 = 4 * (G % 2);
     static_for<0, 4>([&](auto i) {
         constexpr int ks = ks0 + decltype(i)::value;
-        ka[decltype(i)::value] = ds_read_b128_at<mb * 32 * ROWB>(kaddr + k_roff[ks]);
+        ka[decltype(i)::value] = ds_read_b128_at<BASE + mb * 32 * ROWB>(k_addr[ks]);
     });
 }
 
