@@ -17,6 +17,7 @@
  *                           M_ij = 0 where the predicate holds and -inf
  *                           elsewhere, evaluated token by token over ALL N
  *                           keys (brute force), fp64 arithmetic.
+ *   - sta_oracle_attention_lse: the same plus log(sum_j exp(S_ij + M_ij)) per row.
  *   - sta_oracle_probs:     one row of A (for the "rows sum to 1" invariant).
  *   - sta_oracle_tile_order / _tile_permute / _untile:
  *                           the tile-contiguous token order of Sec. 3.1
@@ -93,7 +94,8 @@ static void unravel(long i, const int L[3], int c[3])
 static void attention_one_query(const float *q, const float *k, const float *v,
                                 long N, int d, const int L[3], const int W[3],
                                 const int T[3], double scale, long i,
-                                double *srow, double *out_row, double *row_sum)
+                                double *srow, double *out_row, double *row_sum,
+                                double *lse)
 {
     int qc[3], kc[3];
     unravel(i, L, qc);
@@ -117,6 +119,8 @@ static void attention_one_query(const float *q, const float *k, const float *v,
         srow[j] = exp(srow[j] - m);          /* exp(-inf) = 0 */
         denom += srow[j];
     }
+    /* log of the softmax denominator, log(sum_j exp(S_ij + M_ij)) */
+    if (lse) *lse = m + log(denom);
     for (long j = 0; j < N; ++j) srow[j] /= denom;
     /* O = A V */
     if (out_row) {
@@ -134,10 +138,11 @@ static void attention_one_query(const float *q, const float *k, const float *v,
     }
 }
 
-int sta_oracle_attention(const float *q, const float *k, const float *v,
-                         int d, const int L[3], const int T[3], const int W[3],
-                         double scale, const int64_t *query_idx, long nq,
-                         double *out)
+/* lse (optional, [nq]): natural log of the softmax denominator of each query row. */
+int sta_oracle_attention_lse(const float *q, const float *k, const float *v,
+                             int d, const int L[3], const int T[3], const int W[3],
+                             double scale, const int64_t *query_idx, long nq,
+                             double *out, double *lse)
 {
     long N = (long)L[0] * L[1] * L[2];
     int failed = 0;
@@ -153,11 +158,20 @@ int sta_oracle_attention(const float *q, const float *k, const float *v,
 #pragma omp for schedule(dynamic, 4)
             for (long n = 0; n < nq; ++n)
                 attention_one_query(q, k, v, N, d, L, W, T, scale,
-                                    (long)query_idx[n], srow, out + n * d, NULL);
+                                    (long)query_idx[n], srow, out + n * d, NULL,
+                                    lse ? lse + n : NULL);
         }
         free(srow);
     }
     return failed ? -1 : 0;
+}
+
+int sta_oracle_attention(const float *q, const float *k, const float *v,
+                         int d, const int L[3], const int T[3], const int W[3],
+                         double scale, const int64_t *query_idx, long nq,
+                         double *out)
+{
+    return sta_oracle_attention_lse(q, k, v, d, L, T, W, scale, query_idx, nq, out, NULL);
 }
 
 /* One row of A (probabilities over all N keys) and its sum. */
@@ -167,7 +181,7 @@ int sta_oracle_probs(const float *q, const float *k, int d, const int L[3],
 {
     long N = (long)L[0] * L[1] * L[2];
     attention_one_query(q, k, NULL, N, d, L, W, T, scale, i, probs, NULL,
-                        row_sum);
+                        row_sum, NULL);
     return 0;
 }
 

@@ -32,6 +32,9 @@ def _load():
     lib.sta_oracle_attention.argtypes = [c_void, c_void, c_void, c_int, _I3, _I3, _I3, c_double,
                                          c_void, c_long, c_void]
     lib.sta_oracle_attention.restype = c_int
+    lib.sta_oracle_attention_lse.argtypes = [c_void, c_void, c_void, c_int, _I3, _I3, _I3, c_double,
+                                             c_void, c_long, c_void, c_void]
+    lib.sta_oracle_attention_lse.restype = c_int
     lib.sta_oracle_probs.argtypes = [c_void, c_void, c_int, _I3, _I3, _I3, c_double, c_long,
                                      c_void, c_void]
     lib.sta_oracle_probs.restype = c_int
@@ -76,11 +79,12 @@ def keep(q, k, grid, window_tokens, tile) -> bool:
     return bool(_load().sta_oracle_keep(_i3(q), _i3(k), _i3(grid), _i3(window_tokens), _i3(tile)))
 
 
-def attention(q, k, v, grid, tile, window_tokens, scale=None, query_idx=None):
+def attention(q, k, v, grid, tile, window_tokens, scale=None, query_idx=None, return_lse=False):
     """Masked attention (Eq. 1) of ONE head in raster order.
 
     q, k, v: [N, d] arrays (any float type; values are taken exactly as fp32).
-    query_idx: raster indices to evaluate (default: all).  Returns [nq, d] fp64.
+    query_idx: raster indices to evaluate (default: all).  Returns [nq, d] fp64, and with
+    return_lse also [nq] fp64: the natural log of each row's softmax denominator.
     """
     lib = _load()
     q, k, v = _f32(q), _f32(k), _f32(v)
@@ -93,12 +97,13 @@ def attention(q, k, v, grid, tile, window_tokens, scale=None, query_idx=None):
     query_idx = np.ascontiguousarray(query_idx, dtype=np.int64)
     assert query_idx.ndim == 1 and (query_idx >= 0).all() and (query_idx < N).all()
     out = np.empty((query_idx.shape[0], d), dtype=np.float64)
-    rc = lib.sta_oracle_attention(q.ctypes.data, k.ctypes.data, v.ctypes.data, d, _i3(grid), _i3(tile),
-                                  _i3(window_tokens), float(scale), query_idx.ctypes.data,
-                                  query_idx.shape[0], out.ctypes.data)
+    lse = np.empty(query_idx.shape[0], dtype=np.float64)
+    rc = lib.sta_oracle_attention_lse(q.ctypes.data, k.ctypes.data, v.ctypes.data, d, _i3(grid), _i3(tile),
+                                      _i3(window_tokens), float(scale), query_idx.ctypes.data,
+                                      query_idx.shape[0], out.ctypes.data, lse.ctypes.data)
     if rc != 0:
         raise MemoryError("oracle attention failed")
-    return out
+    return (out, lse) if return_lse else out
 
 
 def attention_bh(q, k, v, grid, tile, window_tokens_per_head, scale=None, query_idx=None):

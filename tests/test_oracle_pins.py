@@ -327,3 +327,48 @@ def test_non_multiple_grid_is_rejected():
         orc.tile_order((5, 4, 4), (2, 2, 2))
     with pytest.raises(ValueError):
         orc.key_tiles((4, 4, 5), (2, 2, 2), (2, 2, 2))
+
+
+# --------------------------------------------------------------------------
+# Log of the softmax denominator, and the attention recall built from it
+# --------------------------------------------------------------------------
+def test_lse_full_window_is_library_logsumexp():
+    from scipy.special import logsumexp
+    grid, tile = (2, 6, 4), (1, 3, 2)
+    N, d = int(np.prod(grid)), 16
+    q, k, v = _rand((N, d), 31), _rand((N, d), 32), _rand((N, d), 33)
+    out, lse = orc.attention(q, k, v, grid, tile, grid, return_lse=True)
+    s = (q.astype(np.float64) @ k.astype(np.float64).T) / np.sqrt(d)
+    np.testing.assert_allclose(lse, logsumexp(s, axis=1), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(out, _dense_softmax_attention(q, k, v, 1.0 / np.sqrt(d)), rtol=1e-12, atol=1e-13)
+
+
+def test_lse_unit_window_is_per_tile_logsumexp():
+    from scipy.special import logsumexp
+    grid, tile = (4, 4, 6), (2, 2, 3)
+    N, d = int(np.prod(grid)), 8
+    q, k, v = _rand((N, d), 34), _rand((N, d), 35), _rand((N, d), 36)
+    _, lse = orc.attention(q, k, v, grid, tile, tile, scale=0.7, return_lse=True)
+    coords = np.stack(np.unravel_index(np.arange(N), grid), axis=1)
+    tile_of = coords // np.array(tile)
+    for tc in itertools.product(*[range(g // t) for g, t in zip(grid, tile)]):
+        idx = np.nonzero((tile_of == np.array(tc)).all(axis=1))[0]
+        s = (q[idx].astype(np.float64) @ k[idx].astype(np.float64).T) * 0.7
+        np.testing.assert_allclose(lse[idx], logsumexp(s, axis=1), rtol=1e-13, atol=1e-13)
+
+
+def test_recall_from_lse_equals_probability_mass_inside_the_window():
+    """Attention recall (Sec. 1: the fraction of the total attention score that falls inside a local
+    window) of query i is sum_{j kept} A_full[i, j].  It must equal exp(lse_window - lse_full)."""
+    grid, tile, win = (2, 6, 6), (1, 2, 2), (1, 6, 2)
+    N, d = int(np.prod(grid)), 8
+    q, k, v = _rand((N, d), 37) * 2.0, _rand((N, d), 38) * 2.0, _rand((N, d), 39)
+    _, lse_w = orc.attention(q, k, v, grid, tile, win, return_lse=True)
+    _, lse_f = orc.attention(q, k, v, grid, tile, grid, return_lse=True)
+    recall = np.exp(lse_w - lse_f)
+    assert (recall > 0).all() and (recall <= 1 + 1e-14).all()
+    for i in (0, 5, 33, N - 1):
+        p_full, _ = orc.probs(q, k, grid, tile, grid, i)
+        qc = np.unravel_index(i, grid)
+        inside = np.array([orc.keep(qc, np.unravel_index(j, grid), grid, win, tile) for j in range(N)])
+        np.testing.assert_allclose(recall[i], p_full[inside].sum(), rtol=1e-12)
