@@ -79,6 +79,64 @@ int sta_forward(const void *q_tiled, const void *k_tiled, const void *v_tiled,
                 const int tile[3], const int *window_tiles, float scale,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * sta_forward that also returns, per query row, the natural log of the softmax
+ * denominator of Eq. 1, ln(sum_j exp(S_ij + M_ij)).  lse_tiled: device, float32,
+ * [B, H, N] in TILED token order; must not overlap the other buffers.  It is the
+ * quantity from which the paper's attention recall (Sec. 1: the fraction of the
+ * total attention score inside a local window) follows without another pass over
+ * the scores: recall = exp(lse_window - lse_full).  Everything else as sta_forward.
+ */
+int sta_forward_lse(const void *q_tiled, const void *k_tiled, const void *v_tiled,
+                    void *o_tiled, float *lse_tiled, int B, int H, int D,
+                    const int grid[3], const int tile[3], const int *window_tiles,
+                    float scale, void *hip_stream);
+
+/*
+ * Per-head mean squared error between two attention outputs, the loss of the
+ * paper's mask-search algorithm ("STA Mask Search": loss <- MSE(O, O')).
+ * a, b: device, bf16, [B, H, N, D] in the same token order.  dev_mse: device,
+ * float32 [H]; entry h is the mean over batch, tokens and channels of
+ * (a - b)^2 for head h, accumulated in fp32 per thread and fp64 across threads
+ * in a fixed order (repeatable).  workspace: device, 8-byte aligned, at least
+ * sta_head_mse_workspace_bytes(B, H) bytes, else STA_ERR_WORKSPACE.
+ */
+size_t sta_head_mse_workspace_bytes(int B, int H);
+int sta_head_mse(const void *a, const void *b, int B, int H, int D,
+                 const int grid[3], void *workspace, size_t workspace_bytes,
+                 float *dev_mse, void *hip_stream);
+
+/*
+ * Inner loop of the paper's mask-search algorithm for one layer and one set of
+ * activations: O <- full attention; for every pattern p of the list (window
+ * sizes in tiles, host, [n_patterns][3]): O' <- STA with window p, loss <-
+ * MSE(O, O') per head; the pattern kept for a head is the first one whose loss
+ * is strictly smaller than every earlier one.  dev_losses: device float32
+ * [n_patterns][H]; dev_best: device int32 [H] (index into the list).  o_full,
+ * o_pattern: device scratch tensors, bf16 [B, H, N, D], caller-provided;
+ * workspace as for sta_head_mse.  Averaging the losses over prompts and time
+ * steps, as the paper does before the final choice, is left to the caller
+ * (dev_losses is there for that).  H <= 4096.
+ */
+int sta_mask_search(const void *q_tiled, const void *k_tiled, const void *v_tiled,
+                    int B, int H, int D, const int grid[3], const int tile[3],
+                    const int *patterns, int n_patterns, float scale,
+                    void *o_full, void *o_pattern, void *workspace,
+                    size_t workspace_bytes, float *dev_losses, int32_t *dev_best,
+                    void *hip_stream);
+
+/*
+ * Attention recall (Sec. 1: the fraction of the total attention score that
+ * falls inside a local window) from the two log-denominators sta_forward_lse
+ * returns for the window and for the full grid: recall = exp(lse_window -
+ * lse_full) per query.  lse_*: device float32 [B, H, N] (same token order).
+ * dev_recall: device float32 [B, H, N] or NULL; dev_mean: device float32
+ * [B*H], the mean recall of each (batch, head).
+ */
+int sta_attention_recall(const float *lse_window, const float *lse_full, int B,
+                         int H, const int grid[3], float *dev_recall,
+                         float *dev_mean, void *hip_stream);
+
 /* Bytes of device scratch sta_forward needs for this problem (0 if none). */
 size_t sta_workspace_bytes(int B, int H, int D, const int grid[3],
                            const int tile[3]);

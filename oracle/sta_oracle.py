@@ -187,3 +187,33 @@ def block_census(grid, tile, window_tokens):
                                    *[ctypes.addressof(v) for v in vals]) != 0:
         raise ValueError("grid is not a multiple of tile")
     return tuple(int(v.value) for v in vals)
+
+
+def head_mse(o_ref, o_other):
+    """MSE(O, O') per head over batch, tokens and channels ("STA Mask Search": loss <- MSE(O, O')).
+    o_*: [B, H, n, d] arrays; returns [H] fp64."""
+    a = np.asarray(o_ref, dtype=np.float64)
+    b = np.asarray(o_other, dtype=np.float64)
+    diff = a - b
+    return (diff * diff).mean(axis=(0, 2, 3))
+
+
+def mask_search(q, k, v, grid, tile, patterns_tokens, scale=None, query_idx=None):
+    """Inner loop of the paper's mask-search algorithm for one layer: O <- original (full) attention output;
+    for each pattern p in list order: O' <- output with window p, loss <- MSE(O, O'); a pattern replaces the
+    best one only if its loss is strictly smaller.  q, k, v: [B, H, N, d].  Returns (losses [n_p, H], best [H]).
+    query_idx restricts the MSE to a sample of query rows (same rows for every pattern)."""
+    B, H = q.shape[0], q.shape[1]
+    full = [list(grid)] * H
+    o = attention_bh(q, k, v, grid, tile, full, scale=scale, query_idx=query_idx)
+    losses = np.empty((len(patterns_tokens), H), dtype=np.float64)
+    best = np.full(H, -1, dtype=np.int64)
+    minimum = np.full(H, np.inf)
+    for p, pat in enumerate(patterns_tokens):
+        o_p = attention_bh(q, k, v, grid, tile, [list(pat)] * H, scale=scale, query_idx=query_idx)
+        losses[p] = head_mse(o, o_p)
+        for h in range(H):
+            if losses[p, h] < minimum[h]:
+                minimum[h] = losses[p, h]
+                best[h] = p
+    return losses, best

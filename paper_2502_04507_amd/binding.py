@@ -15,8 +15,9 @@ STA_BF16, STA_F32 = 0, 1
 _I3 = ctypes.c_int * 3
 
 EXPORTED_SYMBOLS = (
-    "sta_tile_permute", "sta_untile", "sta_forward", "sta_workspace_bytes", "sta_key_tile_box",
+    "sta_tile_permute", "sta_untile", "sta_forward", "sta_forward_lse", "sta_workspace_bytes", "sta_key_tile_box",
     "sta_dump_key_tiles", "sta_window_tokens_to_tiles", "sta_kept_flops", "sta_strerror", "sta_version",
+    "sta_head_mse_workspace_bytes", "sta_head_mse", "sta_mask_search", "sta_attention_recall",
 )
 
 
@@ -48,6 +49,17 @@ def load_library():
     lib.sta_forward.argtypes = [vp, vp, vp, vp, ci, ci, ci, _I3, _I3, ctypes.POINTER(ci), cf, vp,
                                 ctypes.c_size_t, vp]
     lib.sta_forward.restype = ci
+    lib.sta_forward_lse.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, _I3, _I3, ctypes.POINTER(ci), cf, vp]
+    lib.sta_forward_lse.restype = ci
+    lib.sta_head_mse_workspace_bytes.argtypes = [ci, ci]
+    lib.sta_head_mse_workspace_bytes.restype = ctypes.c_size_t
+    lib.sta_head_mse.argtypes = [vp, vp, ci, ci, ci, _I3, vp, ctypes.c_size_t, vp, vp]
+    lib.sta_head_mse.restype = ci
+    lib.sta_mask_search.argtypes = [vp, vp, vp, ci, ci, ci, _I3, _I3, ctypes.POINTER(ci), ci, cf, vp, vp, vp,
+                                    ctypes.c_size_t, vp, vp, vp]
+    lib.sta_mask_search.restype = ci
+    lib.sta_attention_recall.argtypes = [vp, vp, ci, ci, _I3, vp, vp, vp]
+    lib.sta_attention_recall.restype = ci
     lib.sta_workspace_bytes.argtypes = [ci, ci, ci, _I3, _I3]
     lib.sta_workspace_bytes.restype = ctypes.c_size_t
     lib.sta_key_tile_box.argtypes = [_I3, _I3, _I3, _I3, _I3]
@@ -160,6 +172,23 @@ def sta_forward(q_tiled, k_tiled, v_tiled, o_tiled, grid, tile, window_tiles, sc
     return o_tiled
 
 
+def sta_forward_lse(q_tiled, k_tiled, v_tiled, o_tiled, lse_tiled, grid, tile, window_tiles, scale=0.0, stream=None):
+    """sta_forward that also writes lse_tiled (float32 [B,H,N], tiled order): ln of each row's softmax denominator."""
+    lib = load_library()
+    for t in (q_tiled, k_tiled, v_tiled, o_tiled):
+        if t.dim() != 4 or t.shape != q_tiled.shape or t.dtype != torch.bfloat16:
+            raise ValueError("expect four bf16 [B, H, N, D] tensors of equal shape")
+    B, H, N, D = q_tiled.shape
+    if lse_tiled.dtype != torch.float32 or tuple(lse_tiled.shape) != (B, H, N):
+        raise ValueError("lse_tiled must be float32 [B, H, N]")
+    if N != int(grid[0]) * int(grid[1]) * int(grid[2]):
+        raise ValueError("N does not match the grid")
+    _check(lib.sta_forward_lse(_dev(q_tiled, "q"), _dev(k_tiled, "k"), _dev(v_tiled, "v"), _dev(o_tiled, "o"),
+                               _dev(lse_tiled, "lse"), B, H, D, _i3(grid), _i3(tile), _windows(window_tiles, H),
+                               float(scale), _stream_ptr(stream)))
+    return o_tiled, lse_tiled
+
+
 def sta_key_tile_box(grid_tiles, window_tiles, q_tile):
     """Host-side, pure integer: inclusive (lo, hi) box of kept key tiles."""
     lo, hi = _I3(), _I3()
@@ -189,3 +218,55 @@ def sta_window_tokens_to_tiles(window_tokens, tile):
 
 def sta_kept_flops(B, H, D, grid, tile, window_tiles) -> float:
     return float(load_library().sta_kept_flops(B, H, D, _i3(grid), _i3(tile), _windows(window_tiles, H)))
+
+
+def sta_head_mse_workspace_bytes(B, H) -> int:
+    return int(load_library().sta_head_mse_workspace_bytes(int(B), int(H)))
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def sta_head_mse(a, b, grid, workspace, mse, stream=None):
+    """Per-head MSE of two bf16 [B,H,N,D] tensors into mse (float32 [H]); workspace: device bytes."""
+    if a.shape != b.shape or a.dtype != torch.bfloat16 or b.dtype != torch.bfloat16 or a.dim() != 4:
+        raise ValueError("expect two bf16 [B, H, N, D] tensors of equal shape")
+    B, H, N, D = a.shape
+    if mse.dtype != torch.float32 or mse.numel() != H:
+        raise ValueError("mse must be float32 [H]")
+    _check(load_library().sta_head_mse(_dev(a, "a"), _dev(b, "b"), B, H, D, _i3(grid), _dev(workspace, "workspace"),
+                                       _nbytes(workspace), _dev(mse, "mse"), _stream_ptr(stream)))
+    return mse
+
+
+def sta_mask_search(q_tiled, k_tiled, v_tiled, grid, tile, patterns, o_full, o_pattern, workspace, losses, best,
+                    scale=0.0, stream=None):
+    """Mask-search inner loop: losses float32 [n_patterns, H], best int32 [H]; patterns: (t,h,w) in tiles."""
+    B, H, N, D = q_tiled.shape
+    flat = [int(x) for p in patterns for x in p]
+    n_p = len(patterns)
+    if len(flat) != 3 * n_p:
+        raise ValueError("patterns must be triples")
+    if losses.dtype != torch.float32 or losses.numel() != n_p * H or best.dtype != torch.int32 or best.numel() != H:
+        raise ValueError("losses must be float32 [n_patterns, H] and best int32 [H]")
+    arr = (ctypes.c_int * (3 * n_p))(*flat)
+    _check(load_library().sta_mask_search(_dev(q_tiled, "q"), _dev(k_tiled, "k"), _dev(v_tiled, "v"), B, H, D,
+                                          _i3(grid), _i3(tile), arr, n_p, float(scale), _dev(o_full, "o_full"),
+                                          _dev(o_pattern, "o_pattern"), _dev(workspace, "workspace"),
+                                          _nbytes(workspace), _dev(losses, "losses"), _dev(best, "best"),
+                                          _stream_ptr(stream)))
+    return losses, best
+
+
+def sta_attention_recall(lse_window, lse_full, grid, mean, recall=None, stream=None):
+    """recall = exp(lse_window - lse_full); mean: float32 [B*H]; recall: optional float32 [B,H,N]."""
+    if lse_window.shape != lse_full.shape or lse_window.dim() != 3 or lse_window.dtype != torch.float32:
+        raise ValueError("expect two float32 [B, H, N] tensors")
+    B, H, N = lse_window.shape
+    if mean.dtype != torch.float32 or mean.numel() != B * H:
+        raise ValueError("mean must be float32 [B*H]")
+    rp = ctypes.c_void_p(0) if recall is None else _dev(recall, "recall")
+    _check(load_library().sta_attention_recall(_dev(lse_window, "lse_window"), _dev(lse_full, "lse_full"), B, H,
+                                               _i3(grid), rp, _dev(mean, "mean"), _stream_ptr(stream)))
+    return mean

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libsta.so")
 BUILD_DIR = os.path.join(HERE, "_build")
-SOURCES = ["sta_api.hip", "sta_permute.hip", "sta_attention.hip"]
+SOURCES = ["sta_api.hip", "sta_permute.hip", "sta_attention.hip", "sta_reduce.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -16,6 +16,9 @@ FLAGS = [
     # packed fp32 instructions are kept out of every kernel
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
+    # no NaN is ever produced inside the kernels (the only infinities are the initial running maxima, which meet
+    # finite values only); saying so lets max chains compile to v_max3_f32 without per-operand canonicalisation
+    "-fno-honor-nans",
 ]
 
 

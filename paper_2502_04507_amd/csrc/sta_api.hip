@@ -149,6 +149,7 @@ sta::FwdParams make_fwd_params(const Shape &s, int H, float scale_log2e)
     p.head_base = 0;
     p.heads = 0;
     p.scale_log2e = scale_log2e;
+    p.lse = nullptr;
     return p;
 }
 
@@ -170,12 +171,14 @@ int sta_untile(const void *src, void *dst, int src_dt, int dst_dt, int B, int H,
 
 size_t sta_workspace_bytes(int, int, int, const int *, const int *) { return 0; }
 
-int sta_forward(const void *q_tiled, const void *k_tiled, const void *v_tiled, void *o_tiled, int B, int H, int D,
-                const int grid[3], const int tile[3], const int *window_tiles, float scale, void *workspace,
-                size_t workspace_bytes, void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+int forward_common(const void *q_tiled, const void *k_tiled, const void *v_tiled, void *o_tiled, float *lse_tiled,
+                   int B, int H, int D, const int grid[3], const int tile[3], const int *window_tiles, float scale,
+                   void *hip_stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     if (!q_tiled || !k_tiled || !v_tiled || !o_tiled) return STA_ERR_NULL;
     Shape s;
     if (int rc = check_shape(B, H, D, grid, tile, &s)) return rc;
@@ -187,6 +190,13 @@ int sta_forward(const void *q_tiled, const void *k_tiled, const void *v_tiled, v
         return STA_ERR_ALIAS;
     if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
     sta::FwdParams p = make_fwd_params(s, H, scale * 1.4426950408889634f);
+    if (lse_tiled) {
+        const size_t lse_bytes = (size_t)B * H * s.N * sizeof(float);
+        if (ranges_overlap(lse_tiled, lse_bytes, q_tiled, bytes) || ranges_overlap(lse_tiled, lse_bytes, k_tiled, bytes) ||
+            ranges_overlap(lse_tiled, lse_bytes, v_tiled, bytes) || ranges_overlap(lse_tiled, lse_bytes, o_tiled, bytes))
+            return STA_ERR_ALIAS;
+        p.lse = lse_tiled;
+    }
 
     // Per-head windows travel in the kernel arguments; heads are launched in chunks.
     int max_heads = sta::kMaxHeadsPerLaunch;
@@ -205,6 +215,98 @@ int sta_forward(const void *q_tiled, const void *k_tiled, const void *v_tiled, v
         if (e != hipSuccess) return STA_ERR_HIP;
     }
     return STA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sta_forward(const void *q_tiled, const void *k_tiled, const void *v_tiled, void *o_tiled, int B, int H, int D,
+                const int grid[3], const int tile[3], const int *window_tiles, float scale, void *workspace,
+                size_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    return forward_common(q_tiled, k_tiled, v_tiled, o_tiled, nullptr, B, H, D, grid, tile, window_tiles, scale,
+                          hip_stream);
+}
+
+int sta_forward_lse(const void *q_tiled, const void *k_tiled, const void *v_tiled, void *o_tiled, float *lse_tiled,
+                    int B, int H, int D, const int grid[3], const int tile[3], const int *window_tiles, float scale,
+                    void *hip_stream)
+{
+    if (!lse_tiled) return STA_ERR_NULL;
+    return forward_common(q_tiled, k_tiled, v_tiled, o_tiled, lse_tiled, B, H, D, grid, tile, window_tiles, scale,
+                          hip_stream);
+}
+
+size_t sta_head_mse_workspace_bytes(int B, int H)
+{
+    if (B <= 0 || H <= 0) return 0;
+    return (size_t)B * (size_t)H * sta::kMseSlices * sizeof(double);
+}
+
+int sta_head_mse(const void *a, const void *b, int B, int H, int D, const int grid[3], void *workspace,
+                 size_t workspace_bytes, float *dev_mse, void *hip_stream)
+{
+    if (!a || !b || !dev_mse) return STA_ERR_NULL;
+    const int unit[3] = {1, 1, 1};
+    Shape s;
+    if (int rc = check_shape(B, H, D, grid, unit, &s)) return rc;
+    if (D % 8 != 0) return STA_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < sta_head_mse_workspace_bytes(B, H)) return STA_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 7) != 0) return STA_ERR_WORKSPACE;
+    hipError_t e = sta::launch_head_mse(a, b, B, H, (size_t)s.N * D, static_cast<double *>(workspace), dev_mse,
+                                        static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? STA_OK : STA_ERR_HIP;
+}
+
+int sta_attention_recall(const float *lse_window, const float *lse_full, int B, int H, const int grid[3],
+                         float *dev_recall, float *dev_mean, void *hip_stream)
+{
+    if (!lse_window || !lse_full || !dev_mean) return STA_ERR_NULL;
+    const int unit[3] = {1, 1, 1};
+    Shape s;
+    if (int rc = check_shape(B, H, 8, grid, unit, &s)) return rc;
+    hipError_t e = sta::launch_recall(lse_window, lse_full, B * H, (size_t)s.N, dev_recall, dev_mean,
+                                      static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? STA_OK : STA_ERR_HIP;
+}
+
+int sta_mask_search(const void *q_tiled, const void *k_tiled, const void *v_tiled, int B, int H, int D,
+                    const int grid[3], const int tile[3], const int *patterns, int n_patterns, float scale,
+                    void *o_full, void *o_pattern, void *workspace, size_t workspace_bytes, float *dev_losses,
+                    int32_t *dev_best, void *hip_stream)
+{
+    if (!patterns || !o_full || !o_pattern || !dev_losses || !dev_best) return STA_ERR_NULL;
+    if (n_patterns < 1 || n_patterns > 4096) return STA_ERR_SHAPE;
+    if (H > 4096) return STA_ERR_SHAPE;
+    if (int rc = check_windows(n_patterns, patterns)) return rc;
+    Shape s;
+    if (int rc = check_shape(B, H, D, grid, tile, &s)) return rc;
+    if (!workspace || workspace_bytes < sta_head_mse_workspace_bytes(B, H)) return STA_ERR_WORKSPACE;
+    const size_t bytes = (size_t)B * H * s.N * D * 2;
+    if (ranges_overlap(o_full, bytes, o_pattern, bytes)) return STA_ERR_ALIAS;
+
+    // Every head's output depends on that head's mask only, so one launch with the same pattern on all heads
+    // yields the per-head losses the algorithm obtains by masking one head at a time.
+    int win[3 * 4096];
+    for (int h = 0; h < H; ++h)
+        for (int a = 0; a < 3; ++a) win[3 * h + a] = s.n[a];                 // the original: full attention
+    if (int rc = forward_common(q_tiled, k_tiled, v_tiled, o_full, nullptr, B, H, D, grid, tile, win, scale, hip_stream))
+        return rc;
+    for (int p = 0; p < n_patterns; ++p) {
+        for (int h = 0; h < H; ++h)
+            for (int a = 0; a < 3; ++a) win[3 * h + a] = patterns[3 * p + a];
+        if (int rc = forward_common(q_tiled, k_tiled, v_tiled, o_pattern, nullptr, B, H, D, grid, tile, win, scale,
+                                    hip_stream))
+            return rc;
+        if (int rc = sta_head_mse(o_full, o_pattern, B, H, D, grid, workspace, workspace_bytes,
+                                  dev_losses + (size_t)p * H, hip_stream))
+            return rc;
+    }
+    hipError_t e = sta::launch_first_min(dev_losses, n_patterns, H, dev_best, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? STA_OK : STA_ERR_HIP;
 }
 
 int sta_key_tile_box(const int grid_tiles[3], const int window_tiles[3], const int q_tile[3], int lo[3], int hi[3])

@@ -227,6 +227,10 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
     for (int nq = 0; nq < NQ; ++nq) {
         const float l_tot = l_run[nq] + __shfl_xor(l_run[nq], 32);
         const float inv = 1.f / l_tot;
+        // sum_j exp(s_j * scale) = 2^(m * scale_log2e) * l  =>  ln = m * scale_log2e * ln 2 + ln l
+        if (p.lse != nullptr && hb == 0)
+            p.lse[bh * p.N + (size_t)qblock * C::kQB + (size_t)wave * NQ * 32 + nq * 32 + lo] =
+                m_run[nq] * p.scale_log2e * 0.6931471805599453f + __logf(l_tot);
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -517,7 +521,11 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
 
     // ---- finalize -------------------------------------------------------------------
     bf16_raw *oh = o + (bh * p.N + (size_t)qblock * QB + (size_t)wave * 32) * D;
-    const float inv = 1.f / half_swap_sum(l_run);
+    const float l_tot = half_swap_sum(l_run);
+    const float inv = 1.f / l_tot;
+    // sum_j exp(s_j * scale) = 2^(m * scale_log2e) * l  =>  ln = m * scale_log2e * ln 2 + ln l
+    if (p.lse != nullptr && hb == 0)
+        p.lse[bh * p.N + (size_t)qblock * QB + (size_t)wave * 32 + lo] = m_run * c * 0.6931471805599453f + __logf(l_tot);
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll

@@ -22,13 +22,11 @@ __device__ __forceinline__ floatx16 mfma_32x32x16(bf16x8 a, bf16x8 b, floatx16 c
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 #define STA_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
-// max(a, b, c) in one instruction (the compiler would add a canonicalising max per MFMA result first).
-__device__ __forceinline__ float max3(float a, float b, float c)
-{
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
+// max(a, b, c).  Written with fmaxf so that the compiler sees the reads of MFMA results and inserts the wait
+// states the hardware needs between a matrix instruction and a vector read of its result (it does not do that
+// for inline assembly).  The translation unit is built with -fno-honor-nans, which lets this become a single
+// v_max3_f32 without a canonicalising max per operand.
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
 __device__ __forceinline__ float half_swap_max(float x)
 {

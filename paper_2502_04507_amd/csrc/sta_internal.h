@@ -42,6 +42,7 @@ struct FwdParams {
     uint32_t head_base;    // first head of this launch
     uint32_t heads;        // heads in this launch
     float scale_log2e;     // softmax scale * log2(e)
+    float *lse;            // optional output [B,H,N] (tiled order): ln of each row's softmax denominator; may be null
 };
 
 // Returns hipErrorInvalidValue if no kernel instance exists for (P, D).
@@ -50,6 +51,14 @@ hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, 
                           hipStream_t stream);
 bool forward_supported(int P, int D);
 extern bool g_force_generic;   // debugging aid: route every shape through the generic kernel
+
+// ---- reductions around the attention kernel ----------------------------------
+constexpr int kMseSlices = 64;     // partial sums per (batch, head) slab
+hipError_t launch_head_mse(const void *a, const void *b, int B, int H, size_t elems_per_head, double *partial,
+                           float *mse_per_head, hipStream_t stream);
+hipError_t launch_first_min(const float *losses, int n_patterns, int H, int32_t *best, hipStream_t stream);
+hipError_t launch_recall(const float *lse_window, const float *lse_full, int BH, size_t N, float *recall,
+                         float *mean_bh, hipStream_t stream);
 
 hipError_t launch_dump_key_tiles(const FwdParams &p, const WindowTable &win, int32_t *counts,
                                  int32_t *lists, hipStream_t stream);

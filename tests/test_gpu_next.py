@@ -1,0 +1,167 @@
+"""GPU parity tests for the pieces built on top of the attention kernel: the log-denominator output,
+attention recall, per-head MSE and the mask-search inner loop.  All through the C ABI, against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_04507_amd as sta
+import synth_inputs as syn
+from oracle import sta_oracle as orc
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+# ln of the softmax denominator: sums of bf16-rounded probabilities (relative rounding 2^-9 each, averaging
+# out over hundreds of keys) in fp32; an absolute error of 2e-3 in the log is a 0.2 % error of the sum.
+LSE_ABS_TOL = 2e-3
+
+
+def _tiled_inputs(w, q, k, v):
+    qd, kd, vd = (x.to(DEV) for x in (q, k, v))
+    qt, kt, vt = (torch.empty(qd.shape, dtype=torch.bfloat16, device=DEV) for _ in range(3))
+    sta.sta_tile_permute(qd, qt, w.grid, w.tile)
+    sta.sta_tile_permute(kd, kt, w.grid, w.tile)
+    sta.sta_tile_permute(vd, vt, w.grid, w.tile)
+    return qt, kt, vt
+
+
+def _gpu_lse(w, qt, kt, vt, windows):
+    o = torch.empty_like(qt)
+    lse = torch.full(qt.shape[:3], float("nan"), dtype=torch.float32, device=DEV)
+    sta.sta_forward_lse(qt, kt, vt, o, lse, w.grid, w.tile, windows)
+    torch.cuda.synchronize()
+    return o, lse
+
+
+@pytest.mark.parametrize("name,B,H,D,grid,tile,windows", [
+    ("lse-p384", 1, 2, 128, (6, 16, 24), (6, 8, 8), [(1, 3, 3), (1, 1, 2)]),      # 12-wave kernel
+    ("lse-p128", 2, 2, 128, (2, 16, 16), (2, 8, 8), [(1, 2, 1), (1, 9, 9)]),      # 4-wave kernel
+    ("lse-d64", 1, 2, 64, (2, 8, 16), (1, 8, 8), [(1, 1, 3), (3, 1, 1)]),         # generic kernel
+])
+def test_lse_parity(name, B, H, D, grid, tile, windows):
+    w = syn.custom(name, B, H, D, grid, tile, windows, "bf16", seed=901)
+    q, k, v = syn.make_qkv(w)
+    qt, kt, vt = _tiled_inputs(w, q, k, v)
+    o, lse = _gpu_lse(w, qt, kt, vt, w.window_tiles)
+    order = orc.tile_order(w.grid, w.tile)
+    lse_h = lse.cpu().numpy()
+    o_h = o.cpu().float().numpy()
+    for b in range(B):
+        for h in range(H):
+            ref_o, ref_lse = orc.attention(q[b, h].float().numpy(), k[b, h].float().numpy(), v[b, h].float().numpy(),
+                                           w.grid, w.tile, orc.window_tiles_to_tokens(w.window_tiles[h], w.tile),
+                                           return_lse=True)
+            got = lse_h[b, h]                       # tiled order: slot s holds raster token order[s]
+            assert np.isfinite(got).all()
+            assert np.abs(got - ref_lse[order]).max() <= LSE_ABS_TOL, (name, b, h, np.abs(got - ref_lse[order]).max())
+            gu.assert_parity(o_h[b, h], ref_o[order], "%s b%d h%d" % (name, b, h))      # output unchanged by the extra store
+
+
+def test_lse_parity_full_size_sampled():
+    w = syn.workload("C4")
+    q, k, v = syn.make_qkv(w)
+    qt, kt, vt = _tiled_inputs(w, q, k, v)
+    _, lse = _gpu_lse(w, qt, kt, vt, w.window_tiles)
+    order = orc.tile_order(w.grid, w.tile)
+    inv = np.empty(w.N, dtype=np.int64)
+    inv[order] = np.arange(w.N)
+    lse_h = lse.cpu().numpy()
+    for h in (0, 11, 23):
+        idx = gu.stratified_query_sample(w, 48, [], seed=300 + h)
+        _, ref = orc.attention(q[0, h].float().numpy(), k[0, h].float().numpy(), v[0, h].float().numpy(), w.grid, w.tile,
+                               orc.window_tiles_to_tokens(w.window_tiles[h], w.tile), query_idx=idx, return_lse=True)
+        assert np.abs(lse_h[0, h, inv[idx]] - ref).max() <= LSE_ABS_TOL
+
+
+def test_attention_recall_parity():
+    """recall = exp(lse_window - lse_full); per-query values and per-(batch, head) means against the oracle."""
+    w = syn.custom("recall", 2, 2, 128, (6, 16, 16), (6, 8, 8), [(1, 1, 1), (1, 1, 2)], "bf16", seed=902)
+    q, k, v = syn.make_qkv(w)
+    q = (q.float() * 1.5).to(torch.bfloat16)                     # a little locality-free structure in the scores
+    qt, kt, vt = _tiled_inputs(w, q, k, v)
+    _, lse_w = _gpu_lse(w, qt, kt, vt, w.window_tiles)
+    _, lse_f = _gpu_lse(w, qt, kt, vt, [w.tile_grid] * w.H)
+    recall = torch.full((w.B, w.H, w.N), float("nan"), dtype=torch.float32, device=DEV)
+    mean = torch.full((w.B * w.H,), float("nan"), dtype=torch.float32, device=DEV)
+    sta.sta_attention_recall(lse_w, lse_f, w.grid, mean, recall=recall)
+    torch.cuda.synchronize()
+    order = orc.tile_order(w.grid, w.tile)
+    for b in range(w.B):
+        for h in range(w.H):
+            args = (q[b, h].float().numpy(), k[b, h].float().numpy(), v[b, h].float().numpy(), w.grid, w.tile)
+            _, lw = orc.attention(*args, orc.window_tiles_to_tokens(w.window_tiles[h], w.tile), return_lse=True)
+            _, lf = orc.attention(*args, list(w.grid), return_lse=True)
+            ref = np.exp(lw - lf)[order]
+            got = recall[b, h].cpu().numpy()
+            assert (got > 0).all() and (got <= 1.0 + 4e-3).all()
+            np.testing.assert_allclose(got, ref, rtol=5e-3, atol=1e-6)
+            assert abs(mean[b * w.H + h].item() - ref.mean()) <= 2e-3 * ref.mean()
+    # mean only (no per-query output)
+    mean2 = torch.zeros_like(mean)
+    sta.sta_attention_recall(lse_w, lse_f, w.grid, mean2)
+    torch.cuda.synchronize()
+    assert torch.equal(mean, mean2)
+
+
+def test_head_mse_against_fp64_of_the_same_tensors():
+    g = torch.Generator().manual_seed(903)
+    B, H, N, D = 2, 5, 3 * 5 * 7, 72
+    a = torch.randn((B, H, N, D), generator=g).to(torch.bfloat16)
+    b = (a.float() + 0.1 * torch.randn((B, H, N, D), generator=g)).to(torch.bfloat16)
+    b[:, 3] = a[:, 3]                                                   # identical head: loss exactly zero
+    ws = torch.empty(sta.sta_head_mse_workspace_bytes(B, H), dtype=torch.uint8, device=DEV)
+    mse = torch.full((H,), float("nan"), dtype=torch.float32, device=DEV)
+    sta.sta_head_mse(a.to(DEV), b.to(DEV), (3, 5, 7), ws, mse)
+    torch.cuda.synchronize()
+    ref = orc.head_mse(a.float().numpy(), b.float().numpy())
+    got = mse.cpu().numpy()
+    assert got[3] == 0.0
+    np.testing.assert_allclose(got, ref, rtol=2e-6, atol=0)
+    small = torch.empty(8, dtype=torch.uint8, device=DEV)
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_head_mse(a.to(DEV), b.to(DEV), (3, 5, 7), small, mse)
+    assert e.value.status == 6
+
+
+def test_mask_search_parity():
+    """Losses within 3 % of the oracle's (the GPU compares bf16-rounded outputs), zero for the full window,
+    and the same choice wherever the oracle's two best losses are more than 10 % apart."""
+    w = syn.custom("msearch", 1, 4, 128, (6, 16, 24), (6, 8, 8), [(1, 1, 1)] * 4, "bf16", seed=904)
+    q, k, v = syn.make_qkv(w)
+    # give the heads different locality: head h scales its queries, so windows matter differently
+    for h in range(w.H):
+        q[0, h] = (q[0, h].float() * (0.5 + 0.75 * h)).to(torch.bfloat16)
+    patterns = [(1, 1, 1), (1, 1, 3), (1, 2, 1), (1, 2, 3), (1, 3, 3), (1, 1, 3)]
+    qt, kt, vt = _tiled_inputs(w, q, k, v)
+    o_full, o_pat = torch.empty_like(qt), torch.empty_like(qt)
+    ws = torch.empty(sta.sta_head_mse_workspace_bytes(w.B, w.H), dtype=torch.uint8, device=DEV)
+    losses = torch.full((len(patterns), w.H), float("nan"), dtype=torch.float32, device=DEV)
+    best = torch.full((w.H,), -5, dtype=torch.int32, device=DEV)
+    sta.sta_mask_search(qt, kt, vt, w.grid, w.tile, patterns, o_full, o_pat, ws, losses, best)
+    torch.cuda.synchronize()
+    ref_losses, ref_best = orc.mask_search(q.float().numpy(), k.float().numpy(), v.float().numpy(), w.grid, w.tile,
+                                           [orc.window_tiles_to_tokens(p, w.tile) for p in patterns])
+    got = losses.cpu().numpy()
+    full_idx = patterns.index((1, 2, 3))                     # 1x2x3 tiles is the whole 1x2x3 tile grid
+    assert (got[full_idx] == 0).all() and (ref_losses[full_idx] == 0).all()
+    assert (got[4] == 0).all()                               # a window larger than the grid is the full window too
+    nz = [i for i in range(len(patterns)) if i not in (full_idx, 4)]
+    np.testing.assert_allclose(got[nz], ref_losses[nz], rtol=3e-2)
+    assert (got[1] == got[5]).all()                          # the same pattern twice gives the same loss bit for bit
+    bg = best.cpu().numpy()
+    assert (bg == full_idx).all() and (ref_best == full_idx).all()
+    # without the zero-loss entries the choice is a real comparison
+    pats2 = [(1, 1, 1), (1, 1, 3), (1, 2, 1), (1, 1, 3)]
+    losses2 = torch.zeros((len(pats2), w.H), dtype=torch.float32, device=DEV)
+    sta.sta_mask_search(qt, kt, vt, w.grid, w.tile, pats2, o_full, o_pat, ws, losses2, best)
+    torch.cuda.synchronize()
+    ref_l2, ref_b2 = orc.mask_search(q.float().numpy(), k.float().numpy(), v.float().numpy(), w.grid, w.tile,
+                                     [orc.window_tiles_to_tokens(p, w.tile) for p in pats2])
+    np.testing.assert_allclose(losses2.cpu().numpy(), ref_l2, rtol=3e-2)
+    bg = best.cpu().numpy()
+    for h in range(w.H):
+        srt = np.sort(ref_l2[:3, h])
+        if srt[1] > 1.10 * srt[0]:
+            assert bg[h] == ref_b2[h], (h, ref_l2[:, h], losses2[:, h].cpu().numpy())
+        assert bg[h] != 3                                    # the duplicate at the end never replaces the first

@@ -198,6 +198,28 @@ def test_attention_large_scores_stay_finite():
     gu.assert_parity(out[0, 0], ref, "bigscores")
 
 
+@pytest.mark.parametrize("tile,grid", [((6, 8, 8), (6, 16, 32)), ((2, 8, 8), (4, 16, 16)), ((1, 8, 8), (1, 16, 16))])
+def test_forward_is_bit_reproducible(tile, grid):
+    """The same call twice gives the same bits (a vector read of a matrix-instruction result issued too
+    early once made the rescale decision, and with it the rounding, vary from run to run)."""
+    D = 64 if tile[0] == 1 else 128
+    w = syn.custom("repro", 1, 3, D, grid, tile, [(1, 1, 1), (1, 2, 3), (3, 3, 3)], "bf16", seed=81)
+    q, k, v = syn.make_qkv(w)
+    qd, kd, vd = (x.to(DEV) for x in (q, k, v))
+    qt, kt, vt = (torch.empty_like(qd) for _ in range(3))
+    sta.sta_tile_permute(qd, qt, w.grid, w.tile)
+    sta.sta_tile_permute(kd, kt, w.grid, w.tile)
+    sta.sta_tile_permute(vd, vt, w.grid, w.tile)
+    outs = []
+    for _ in range(4):
+        o = torch.full_like(qt, float("nan"))
+        sta.sta_forward(qt, kt, vt, o, w.grid, w.tile, w.window_tiles)
+        outs.append(o)
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16))
+
+
 def test_attention_explicit_scale():
     w = syn.custom("scale", 1, 1, 64, (2, 8, 16), (1, 8, 8), [(1, 1, 3)], "bf16", seed=5)
     q, k, v = syn.make_qkv(w)

@@ -372,3 +372,47 @@ def test_recall_from_lse_equals_probability_mass_inside_the_window():
         qc = np.unravel_index(i, grid)
         inside = np.array([orc.keep(qc, np.unravel_index(j, grid), grid, win, tile) for j in range(N)])
         np.testing.assert_allclose(recall[i], p_full[inside].sum(), rtol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# Mask-search inner loop ("STA Mask Search")
+# --------------------------------------------------------------------------
+def test_head_mse_is_library_mean_squared_error():
+    from sklearn.metrics import mean_squared_error
+    a, b = _rand((2, 3, 10, 4), 41), _rand((2, 3, 10, 4), 42)
+    got = orc.head_mse(a, b)
+    for h in range(3):
+        want = mean_squared_error(a[:, h].reshape(-1).astype(np.float64), b[:, h].reshape(-1).astype(np.float64))
+        np.testing.assert_allclose(got[h], want, rtol=1e-13)
+
+
+def test_mask_search_full_pattern_has_zero_loss_and_first_minimum_wins():
+    grid, tile = (2, 4, 6), (1, 2, 2)
+    N, d, H = int(np.prod(grid)), 8, 2
+    q, k, v = _rand((1, H, N, d), 43), _rand((1, H, N, d), 44), _rand((1, H, N, d), 45)
+    pats = [(1, 2, 2), (1, 4, 2), tuple(grid), (1, 2, 6), tuple(grid)]
+    losses, best = orc.mask_search(q, k, v, grid, tile, pats)
+    assert (losses[2] == 0).all() and (losses[4] == 0).all()
+    assert (losses[[0, 1, 3]] > 0).all()
+    assert (best == 2).all()                       # the second zero-loss entry does not replace the first
+    # constant V: every window gives the same output up to rounding, so every loss vanishes
+    vconst = np.ones_like(v)
+    losses, _ = orc.mask_search(q, k, vconst, grid, tile, pats)
+    assert np.abs(losses).max() <= 1e-28
+
+
+def test_mask_search_losses_match_dense_library_attention():
+    """Loss of a one-tile window against full attention, both computed by the dense library routine."""
+    grid, tile = (1, 4, 4), (1, 2, 2)
+    N, d = 16, 4
+    q, k, v = _rand((1, 1, N, d), 46), _rand((1, 1, N, d), 47), _rand((1, 1, N, d), 48)
+    losses, best = orc.mask_search(q, k, v, grid, tile, [tile])
+    full = _dense_softmax_attention(q[0, 0], k[0, 0], v[0, 0], 0.5)
+    coords = np.stack(np.unravel_index(np.arange(N), grid), axis=1)
+    tid = np.ravel_multi_index((coords // np.array(tile)).T, (1, 2, 2))
+    local = np.empty_like(full)
+    for t in range(4):
+        idx = np.nonzero(tid == t)[0]
+        local[idx] = _dense_softmax_attention(q[0, 0][idx], k[0, 0][idx], v[0, 0][idx], 0.5)
+    np.testing.assert_allclose(losses[0, 0], ((full - local) ** 2).mean(), rtol=1e-12)
+    assert best[0] == 0
