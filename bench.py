@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line, time sta_forward for a list of uniform windows and the "
                          "per-head mixed table on the 30x48x80 grid (speedup-versus-sparsity curve), one JSON line")
+    ap.add_argument("--extras", action="store_true",
+                    help="instead of the benchmark line, time the entry points built on top of the attention kernel "
+                         "(log-denominator output, recall, per-head MSE, mask search) on the workload, one JSON line")
     ap.add_argument("--profile-only", default=None, choices=[None, "forward", "permute", "layer", "copy"],
                     help="run only this part (for rocprofv3), print nothing else; 'copy' is a plain "
                          "device copy of one tensor, the known-size reference for the traffic counters")
@@ -175,6 +178,43 @@ def main():
                      "tflops": fl / ms / 1e9, "frac_of_peak": fl / ms / 1e9 / BF16_MFMA_PEAK_TFLOPS,
                      "speedup_vs_dense": dense_ms / ms, "ideal_speedup": dense_fl / fl})
         print(json.dumps({"sweep": "sta_forward on grid 30x48x80, tile 6x8x8, H=24, D=128, bf16", "rows": rows}))
+        return
+
+    if args.extras:
+        layer.permute_in()
+        H = w.H
+        lse_w = torch.empty((w.B, H, w.N), dtype=torch.float32, device=device)
+        lse_f = torch.empty_like(lse_w)
+        full = tuple(tuple(w.tile_grid) for _ in range(H))
+        fwd_ms = event_time_ms(layer.forward, 5)
+        lse_ms = event_time_ms(lambda: sta.sta_forward_lse(layer.qt, layer.kt, layer.vt, layer.ot, lse_w, w.grid, w.tile,
+                                                           w.window_tiles), 5)
+        sta.sta_forward_lse(layer.qt, layer.kt, layer.vt, layer.o, lse_f, w.grid, w.tile, full)
+        mean = torch.empty((w.B * H,), dtype=torch.float32, device=device)
+        ws = torch.empty(sta.sta_head_mse_workspace_bytes(w.B, H), dtype=torch.uint8, device=device)
+        recall_ms = event_time_ms(lambda: sta.sta_attention_recall(lse_w, lse_f, w.grid, ws, mean), 20)
+        mse = torch.empty((H,), dtype=torch.float32, device=device)
+        mse_ms = event_time_ms(lambda: sta.sta_head_mse(layer.ot, layer.o, w.grid, ws, mse), 20)
+        patterns = [(1, 3, 3), (3, 3, 3), (3, 3, 5)]
+        losses = torch.empty((len(patterns), H), dtype=torch.float32, device=device)
+        best = torch.empty((H,), dtype=torch.int32, device=device)
+        search_ms = event_time_ms(lambda: sta.sta_mask_search(layer.qt, layer.kt, layer.vt, w.grid, w.tile, patterns,
+                                                              layer.q, layer.k, ws, losses, best), 2, warmup=1)
+        torch.cuda.synchronize()
+        search_flops = sum(sta.sta_kept_flops(w.B, H, w.D, w.grid, w.tile, tuple(tuple(p) for _ in range(H)))
+                           for p in patterns + [tuple(w.tile_grid)])
+        print(json.dumps({
+            "extras": "%s: B=%d H=%d D=%d grid=%s tile=%s" % (w.name, w.B, H, w.D, w.grid, w.tile),
+            "sta_forward_ms": fwd_ms, "sta_forward_lse_ms": lse_ms,
+            "sta_attention_recall_ms": recall_ms,
+            "sta_attention_recall_GBs": 2.0 * lse_w.numel() * 4 / (recall_ms * 1e-3) / 1e9,
+            "sta_head_mse_ms": mse_ms, "sta_head_mse_GBs": 2.0 * tensor_bytes / (mse_ms * 1e-3) / 1e9,
+            "sta_head_mse_frac_hbm": 2.0 * tensor_bytes / (mse_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "sta_mask_search_patterns": ["x".join(map(str, p)) for p in patterns],
+            "sta_mask_search_ms": search_ms, "sta_mask_search_tflops": search_flops / (search_ms * 1e-3) / 1e12,
+            "mean_recall_first_heads": [float(x) for x in mean[:4].cpu()],
+            "best_first_heads": [int(x) for x in best[:4].cpu()],
+        }))
         return
 
     if args.profile_only:

@@ -131,10 +131,12 @@ int sta_mask_search(const void *q_tiled, const void *k_tiled, const void *v_tile
  * returns for the window and for the full grid: recall = exp(lse_window -
  * lse_full) per query.  lse_*: device float32 [B, H, N] (same token order).
  * dev_recall: device float32 [B, H, N] or NULL; dev_mean: device float32
- * [B*H], the mean recall of each (batch, head).
+ * [B*H], the mean recall of each (batch, head), summed in a fixed order.
+ * workspace: as for sta_head_mse (same size), else STA_ERR_WORKSPACE.
  */
 int sta_attention_recall(const float *lse_window, const float *lse_full, int B,
-                         int H, const int grid[3], float *dev_recall,
+                         int H, const int grid[3], void *workspace,
+                         size_t workspace_bytes, float *dev_recall,
                          float *dev_mean, void *hip_stream);
 
 /* Bytes of device scratch sta_forward needs for this problem (0 if none). */

@@ -58,7 +58,7 @@ def load_library():
     lib.sta_mask_search.argtypes = [vp, vp, vp, ci, ci, ci, _I3, _I3, ctypes.POINTER(ci), ci, cf, vp, vp, vp,
                                     ctypes.c_size_t, vp, vp, vp]
     lib.sta_mask_search.restype = ci
-    lib.sta_attention_recall.argtypes = [vp, vp, ci, ci, _I3, vp, vp, vp]
+    lib.sta_attention_recall.argtypes = [vp, vp, ci, ci, _I3, vp, ctypes.c_size_t, vp, vp, vp]
     lib.sta_attention_recall.restype = ci
     lib.sta_workspace_bytes.argtypes = [ci, ci, ci, _I3, _I3]
     lib.sta_workspace_bytes.restype = ctypes.c_size_t
@@ -259,8 +259,9 @@ def sta_mask_search(q_tiled, k_tiled, v_tiled, grid, tile, patterns, o_full, o_p
     return losses, best
 
 
-def sta_attention_recall(lse_window, lse_full, grid, mean, recall=None, stream=None):
-    """recall = exp(lse_window - lse_full); mean: float32 [B*H]; recall: optional float32 [B,H,N]."""
+def sta_attention_recall(lse_window, lse_full, grid, workspace, mean, recall=None, stream=None):
+    """recall = exp(lse_window - lse_full); mean: float32 [B*H]; recall: optional float32 [B,H,N];
+    workspace: device bytes, at least sta_head_mse_workspace_bytes(B, H)."""
     if lse_window.shape != lse_full.shape or lse_window.dim() != 3 or lse_window.dtype != torch.float32:
         raise ValueError("expect two float32 [B, H, N] tensors")
     B, H, N = lse_window.shape
@@ -268,5 +269,6 @@ def sta_attention_recall(lse_window, lse_full, grid, mean, recall=None, stream=N
         raise ValueError("mean must be float32 [B*H]")
     rp = ctypes.c_void_p(0) if recall is None else _dev(recall, "recall")
     _check(load_library().sta_attention_recall(_dev(lse_window, "lse_window"), _dev(lse_full, "lse_full"), B, H,
-                                               _i3(grid), rp, _dev(mean, "mean"), _stream_ptr(stream)))
+                                               _i3(grid), _dev(workspace, "workspace"), _nbytes(workspace), rp,
+                                               _dev(mean, "mean"), _stream_ptr(stream)))
     return mean

@@ -262,13 +262,17 @@ int sta_head_mse(const void *a, const void *b, int B, int H, int D, const int gr
 }
 
 int sta_attention_recall(const float *lse_window, const float *lse_full, int B, int H, const int grid[3],
-                         float *dev_recall, float *dev_mean, void *hip_stream)
+                         void *workspace, size_t workspace_bytes, float *dev_recall, float *dev_mean,
+                         void *hip_stream)
 {
     if (!lse_window || !lse_full || !dev_mean) return STA_ERR_NULL;
     const int unit[3] = {1, 1, 1};
     Shape s;
     if (int rc = check_shape(B, H, 8, grid, unit, &s)) return rc;
-    hipError_t e = sta::launch_recall(lse_window, lse_full, B * H, (size_t)s.N, dev_recall, dev_mean,
+    if (!workspace || workspace_bytes < sta_head_mse_workspace_bytes(B, H)) return STA_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 7) != 0) return STA_ERR_WORKSPACE;
+    hipError_t e = sta::launch_recall(lse_window, lse_full, B * H, (size_t)s.N, dev_recall,
+                                      static_cast<double *>(workspace), dev_mean,
                                       static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? STA_OK : STA_ERR_HIP;
 }

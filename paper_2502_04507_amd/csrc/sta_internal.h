@@ -58,7 +58,7 @@ hipError_t launch_head_mse(const void *a, const void *b, int B, int H, size_t el
                            float *mse_per_head, hipStream_t stream);
 hipError_t launch_first_min(const float *losses, int n_patterns, int H, int32_t *best, hipStream_t stream);
 hipError_t launch_recall(const float *lse_window, const float *lse_full, int BH, size_t N, float *recall,
-                         float *mean_bh, hipStream_t stream);
+                         double *partial, float *mean_bh, hipStream_t stream);
 
 hipError_t launch_dump_key_tiles(const FwdParams &p, const WindowTable &win, int32_t *counts,
                                  int32_t *lists, hipStream_t stream);

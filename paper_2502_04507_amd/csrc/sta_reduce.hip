@@ -85,20 +85,34 @@ __global__ void sta_first_min_kernel(const float *__restrict__ losses, int n_pat
     best[h] = arg;
 }
 
-// grid = B*H workgroups.  recall_i = exp(lse_window_i - lse_full_i); optional per-query output; mean per (b,h).
-__global__ __launch_bounds__(kThreads) void sta_recall_kernel(const float *__restrict__ lse_window,
-                                                              const float *__restrict__ lse_full, size_t N,
-                                                              float *__restrict__ recall, float *__restrict__ mean_bh)
+// grid = (slices, B*H).  recall_i = exp(lse_window_i - lse_full_i); optional per-query output; one partial sum
+// per workgroup.
+__global__ __launch_bounds__(kThreads) void sta_recall_partial_kernel(const float *__restrict__ lse_window,
+                                                                      const float *__restrict__ lse_full, size_t N,
+                                                                      float *__restrict__ recall,
+                                                                      double *__restrict__ partial)
 {
-    const size_t base = (size_t)blockIdx.x * N;
-    double acc = 0.0;
-    for (size_t i = threadIdx.x; i < N; i += kThreads) {
+    const size_t base = (size_t)blockIdx.y * N;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    float acc = 0.f;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < N; i += stride) {
         const float r = __expf(lse_window[base + i] - lse_full[base + i]);
         if (recall) recall[base + i] = r;
-        acc += (double)r;
+        acc += r;
     }
-    const double s = block_sum(acc);
-    if (threadIdx.x == 0) mean_bh[blockIdx.x] = (float)(s / (double)N);
+    const double s = block_sum((double)acc);
+    if (threadIdx.x == 0) partial[(size_t)blockIdx.y * gridDim.x + blockIdx.x] = s;
+}
+
+// One thread per (batch, head): fixed-order sum of the slices.
+__global__ void sta_recall_finish_kernel(const double *__restrict__ partial, int slices, int BH, double inv_n,
+                                         float *__restrict__ mean_bh)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= BH) return;
+    double s = 0.0;
+    for (int k = 0; k < slices; ++k) s += partial[(size_t)i * slices + k];
+    mean_bh[i] = (float)(s * inv_n);
 }
 
 }  // namespace
@@ -126,10 +140,13 @@ hipError_t launch_first_min(const float *losses, int n_patterns, int H, int32_t 
     return hipGetLastError();
 }
 
-hipError_t launch_recall(const float *lse_window, const float *lse_full, int BH, size_t N, float *recall, float *mean_bh,
-                         hipStream_t stream)
+hipError_t launch_recall(const float *lse_window, const float *lse_full, int BH, size_t N, float *recall, double *partial,
+                         float *mean_bh, hipStream_t stream)
 {
-    sta_recall_kernel<<<dim3(BH), dim3(kThreads), 0, stream>>>(lse_window, lse_full, N, recall, mean_bh);
+    sta_recall_partial_kernel<<<dim3(kMseSlices, BH), dim3(kThreads), 0, stream>>>(lse_window, lse_full, N, recall, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    sta_recall_finish_kernel<<<dim3((BH + 63) / 64), dim3(64), 0, stream>>>(partial, kMseSlices, BH, 1.0 / (double)N, mean_bh);
     return hipGetLastError();
 }
 

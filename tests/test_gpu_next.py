@@ -84,7 +84,8 @@ def test_attention_recall_parity():
     _, lse_f = _gpu_lse(w, qt, kt, vt, [w.tile_grid] * w.H)
     recall = torch.full((w.B, w.H, w.N), float("nan"), dtype=torch.float32, device=DEV)
     mean = torch.full((w.B * w.H,), float("nan"), dtype=torch.float32, device=DEV)
-    sta.sta_attention_recall(lse_w, lse_f, w.grid, mean, recall=recall)
+    ws = torch.empty(sta.sta_head_mse_workspace_bytes(w.B, w.H), dtype=torch.uint8, device=DEV)
+    sta.sta_attention_recall(lse_w, lse_f, w.grid, ws, mean, recall=recall)
     torch.cuda.synchronize()
     order = orc.tile_order(w.grid, w.tile)
     for b in range(w.B):
@@ -99,7 +100,7 @@ def test_attention_recall_parity():
             assert abs(mean[b * w.H + h].item() - ref.mean()) <= 2e-3 * ref.mean()
     # mean only (no per-query output)
     mean2 = torch.zeros_like(mean)
-    sta.sta_attention_recall(lse_w, lse_f, w.grid, mean2)
+    sta.sta_attention_recall(lse_w, lse_f, w.grid, ws, mean2)
     torch.cuda.synchronize()
     assert torch.equal(mean, mean2)
 
