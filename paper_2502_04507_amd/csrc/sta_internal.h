@@ -42,7 +42,7 @@ struct FwdParams {
     uint32_t head_base;    // first head of this launch
     uint32_t heads;        // heads in this launch
     float scale_log2e;     // softmax scale * log2(e)
-    float *lse;            // optional output [B,H,N] (tiled order): ln of each row's softmax denominator; may be null
+    float *lse = nullptr;  // optional output [B,H,N] (tiled order): ln of each row's softmax denominator; may be null
 };
 
 // Returns hipErrorInvalidValue if no kernel instance exists for (P, D).
