@@ -44,6 +44,10 @@ typedef enum {
 
 typedef enum { STA_BF16 = 0, STA_F32 = 1 } sta_dtype;
 
+/* Mask definitions of the paper's appendix: the tile-granular STA mask and the token-granular sliding
+ * window with inward-shifted centre ("Mask Definition of 3D NATTEN") it is compared against. */
+typedef enum { STA_MASK_STA = 0, STA_MASK_NATTEN = 1 } sta_mask_kind;
+
 /*
  * Tile permutation (Sec. 3.1, appendix "Tiling in STA"): raster -> tiled.
  * src, dst: device, [B, H, N, D], element types src_dt / dst_dt.  Whole
@@ -163,6 +167,22 @@ int sta_key_tile_box(const int grid_tiles[3], const int window_tiles[3],
 int sta_dump_key_tiles(int H, const int grid[3], const int tile[3],
                        const int *window_tiles, int32_t *dev_counts,
                        int32_t *dev_lists, void *hip_stream);
+
+/*
+ * Block census (Sec. 2.2: dense / mixed / empty attention blocks; Theorem 1 for the tiled sliding
+ * window, Theorem 2 for STA; Table 1).  Tokens are taken in TILED order, so block (i, j) of the
+ * attention map is (query tile i, key tile j), P x P scores.  A block is dense when the mask keeps
+ * every score in it, empty when it keeps none, mixed otherwise.  mask_kind: sta_mask_kind;
+ * window_tokens: window size in tokens per axis (for STA_MASK_STA converted to tiles by floor
+ * division, as the STA mask algorithm does).  Exact counts including the borders (the theorems
+ * ignore them).  Host only, pure integer: both masks are products of per-axis interval tests, so
+ * the per-axis classifications are counted and multiplied; no token pair is enumerated.
+ * dense_per_q, mixed_per_q: host int64 [number of tiles], counts per query tile, either may be
+ * NULL.  totals: host int64 [3] = dense, mixed, empty over the whole map; may be NULL.
+ */
+int sta_block_census(int mask_kind, const int grid[3], const int tile[3],
+                     const int window_tokens[3], int64_t *dense_per_q,
+                     int64_t *mixed_per_q, int64_t totals[3]);
 
 /*
  * Window in tokens (the paper's notation, e.g. (18,24,24)) -> window in

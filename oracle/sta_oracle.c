@@ -29,6 +29,15 @@
  *   - sta_oracle_block_census: dense / mixed / empty classification of every
  *                           (query tile, key tile) block by brute force over
  *                           all its token pairs (Sec. 2.2 taxonomy, Theorem 2).
+ *   - sta_oracle_natten_keep: the sliding-window predicate the paper compares
+ *                           against -- appendix algorithm "Mask Definition of
+ *                           3D NATTEN" (window centre shifted inward at the
+ *                           borders, token granularity).
+ *   - sta_oracle_block_census_per_query: the same classification for either
+ *                           predicate and for either token order (tile-
+ *                           contiguous blocks = "tiled", or blocks of
+ *                           consecutive raster tokens), one count pair per
+ *                           query block (Sec. 2.2; Theorems 1 and 2; Table 1).
  *
  * Readings of the paper taken here (each also listed in the design notes):
  *   - "W_tile / 2" in the mask algorithm is integer floor division.
@@ -307,6 +316,77 @@ int sta_oracle_block_census(const int L[3], const int T[3], const int W[3],
         }
     }
     *n_dense = dense; *n_mixed = mixed; *n_empty = empty;
+    return 0;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Sliding-window predicate: appendix algorithm "Mask Definition of 3D     */
+/* NATTEN".  Token coordinates throughout; W/2 is integer floor division    */
+/* (windows are odd in the paper, e.g. 11: five keys on either side).       */
+/* ---------------------------------------------------------------------- */
+int sta_oracle_natten_keep(const int q[3], const int k[3], const int L[3],
+                           const int W[3])
+{
+    int keep = 1;
+    for (int a = 0; a < 3; ++a) {
+        int half = W[a] / 2;
+        /* window centre, shifted inward near the borders */
+        int q_c = imax(imin(q[a], L[a] - 1 - half), half);
+        keep = keep && (abs(q_c - k[a]) <= half);
+    }
+    return keep;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Census per query block for either predicate and either token order.      */
+/* mask: 0 = STA (needs T), 1 = sliding window (T only shapes the blocks).  */
+/* tiled != 0: block b holds the tokens of tile b (tile-contiguous order);  */
+/* tiled == 0: block b holds raster tokens [b*P, (b+1)*P), P = T0*T1*T2.    */
+/* dense_per_q, mixed_per_q: [number of blocks].                            */
+/* ---------------------------------------------------------------------- */
+static void block_token(long block, long i, int tiled, const int L[3],
+                        const int T[3], int c[3])
+{
+    if (tiled) {
+        int t0[3], ti[3];
+        tile_first_token(block, L, T, t0);
+        unravel(i, T, ti);
+        for (int a = 0; a < 3; ++a) c[a] = t0[a] + ti[a];
+    } else {
+        long P = (long)T[0] * T[1] * T[2];
+        unravel(block * P + i, L, c);
+    }
+}
+
+int sta_oracle_block_census_per_query(int mask, int tiled, const int L[3],
+                                      const int T[3], const int W[3],
+                                      int64_t *dense_per_q, int64_t *mixed_per_q)
+{
+    long N = (long)L[0] * L[1] * L[2];
+    long P = (long)T[0] * T[1] * T[2];
+    if (tiled && (L[0] % T[0] || L[1] % T[1] || L[2] % T[2])) return -1;
+    if (!tiled && N % P) return -1;
+    long nb = N / P;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long qb = 0; qb < nb; ++qb) {
+        int64_t dense = 0, mixed = 0;
+        for (long kb = 0; kb < nb; ++kb) {
+            long kept = 0;
+            for (long a = 0; a < P; ++a) {
+                int qc[3], kc[3];
+                block_token(qb, a, tiled, L, T, qc);
+                for (long b = 0; b < P; ++b) {
+                    block_token(kb, b, tiled, L, T, kc);
+                    kept += mask == 0 ? sta_oracle_keep(qc, kc, L, W, T)
+                                      : sta_oracle_natten_keep(qc, kc, L, W);
+                }
+            }
+            if (kept == P * P) dense++;
+            else if (kept != 0) mixed++;
+        }
+        dense_per_q[qb] = dense;
+        mixed_per_q[qb] = mixed;
+    }
     return 0;
 }
 

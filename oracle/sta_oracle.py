@@ -48,6 +48,10 @@ def _load():
     lib.sta_oracle_key_tiles.restype = c_int
     lib.sta_oracle_block_census.argtypes = [_I3, _I3, _I3, c_void, c_void, c_void]
     lib.sta_oracle_block_census.restype = c_int
+    lib.sta_oracle_natten_keep.argtypes = [_I3, _I3, _I3, _I3]
+    lib.sta_oracle_natten_keep.restype = c_int
+    lib.sta_oracle_block_census_per_query.argtypes = [c_int, c_int, _I3, _I3, _I3, c_void, c_void]
+    lib.sta_oracle_block_census_per_query.restype = c_int
     lib.sta_oracle_num_threads.argtypes = []
     lib.sta_oracle_num_threads.restype = c_int
     _lib = lib
@@ -187,6 +191,28 @@ def block_census(grid, tile, window_tokens):
                                    *[ctypes.addressof(v) for v in vals]) != 0:
         raise ValueError("grid is not a multiple of tile")
     return tuple(int(v.value) for v in vals)
+
+
+def natten_keep(q, k, grid, window_tokens):
+    """Sliding-window predicate for one (query token, key token) pair, coordinates (t, h, w)
+    (appendix algorithm "Mask Definition of 3D NATTEN")."""
+    return bool(_load().sta_oracle_natten_keep(_i3(q), _i3(k), _i3(grid), _i3(window_tokens)))
+
+
+def block_census_per_query(mask, order, grid, tile, window_tokens):
+    """(dense[nb], mixed[nb]) per query block by brute force over all token pairs.
+    mask: "sta" or "natten"; order: "tiled" (block = tile) or "raster" (block = P consecutive raster tokens)."""
+    lib = _load()
+    P = int(tile[0]) * int(tile[1]) * int(tile[2])
+    nb = (int(grid[0]) * int(grid[1]) * int(grid[2])) // P
+    dense = np.empty(nb, dtype=np.int64)
+    mixed = np.empty(nb, dtype=np.int64)
+    rc = lib.sta_oracle_block_census_per_query({"sta": 0, "natten": 1}[mask], {"raster": 0, "tiled": 1}[order],
+                                               _i3(grid), _i3(tile), _i3(window_tokens), dense.ctypes.data,
+                                               mixed.ctypes.data)
+    if rc != 0:
+        raise ValueError("grid is not a multiple of the block shape")
+    return dense, mixed
 
 
 def head_mse(o_ref, o_other):

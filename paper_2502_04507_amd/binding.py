@@ -12,12 +12,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 STA_BF16, STA_F32 = 0, 1
+STA_MASK_STA, STA_MASK_NATTEN = 0, 1
 _I3 = ctypes.c_int * 3
 
 EXPORTED_SYMBOLS = (
     "sta_tile_permute", "sta_untile", "sta_forward", "sta_forward_lse", "sta_workspace_bytes", "sta_key_tile_box",
     "sta_dump_key_tiles", "sta_window_tokens_to_tiles", "sta_kept_flops", "sta_strerror", "sta_version",
-    "sta_head_mse_workspace_bytes", "sta_head_mse", "sta_mask_search", "sta_attention_recall",
+    "sta_head_mse_workspace_bytes", "sta_head_mse", "sta_mask_search", "sta_attention_recall", "sta_block_census",
 )
 
 
@@ -70,6 +71,8 @@ def load_library():
     lib.sta_window_tokens_to_tiles.restype = ci
     lib.sta_kept_flops.argtypes = [ci, ci, ci, _I3, _I3, ctypes.POINTER(ci)]
     lib.sta_kept_flops.restype = ctypes.c_double
+    lib.sta_block_census.argtypes = [ci, _I3, _I3, _I3, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.sta_block_census.restype = ci
     lib.sta_strerror.argtypes = [ci]
     lib.sta_strerror.restype = ctypes.c_char_p
     lib.sta_version.argtypes = []
@@ -214,6 +217,22 @@ def sta_window_tokens_to_tiles(window_tokens, tile):
     out = _I3()
     _check(load_library().sta_window_tokens_to_tiles(_i3(window_tokens), _i3(tile), out))
     return tuple(out)
+
+
+def sta_block_census(mask_kind, grid, tile, window_tokens):
+    """Returns (dense_per_q, mixed_per_q, (dense, mixed, empty)); the per-query arrays are lists of ints."""
+    n = 1
+    for g, t in zip(grid, tile):
+        if int(t) <= 0:
+            raise StaError(2, sta_strerror(2))
+        n *= max(int(g) // int(t), 0)
+    n = max(n, 1)
+    dense = (ctypes.c_int64 * n)()
+    mixed = (ctypes.c_int64 * n)()
+    totals = (ctypes.c_int64 * 3)()
+    _check(load_library().sta_block_census(int(mask_kind), _i3(grid), _i3(tile), _i3(window_tokens), dense, mixed,
+                                           totals))
+    return list(dense), list(mixed), tuple(totals)
 
 
 def sta_kept_flops(B, H, D, grid, tile, window_tiles) -> float:

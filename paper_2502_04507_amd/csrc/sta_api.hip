@@ -3,6 +3,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <new>
+
 #include "../../include/sta.h"
 #include "sta_geometry.h"
 #include "sta_internal.h"
@@ -151,6 +153,56 @@ sta::FwdParams make_fwd_params(const Shape &s, int H, float scale_log2e)
     p.scale_log2e = scale_log2e;
     p.lse = nullptr;
     return p;
+}
+
+// Kept key-token interval [lo, hi] along one axis for query token x.
+//  STA: the key-tile range of x's tile, in tokens.  Sliding window: centre x clamped into
+//  [half, L-1-half] (upper clamp first), keys within half of it, clipped to the axis.
+struct TokenRange {
+    int lo, hi;
+};
+
+TokenRange kept_token_range(int mask_kind, int L, int T, int W, int x)
+{
+    TokenRange r;
+    if (mask_kind == STA_MASK_STA) {
+        const int n = L / T;
+        int w = W / T;
+        if (w > 2 * n) w = 2 * n;
+        const StaAxisRange t = sta_axis_range(n, w, x / T);
+        r.lo = t.lo * T;
+        r.hi = t.hi * T + T - 1;
+    } else {
+        const int half = (W < 2 * L ? W : 2 * L) / 2;
+        int c = x < (L - 1 - half) ? x : (L - 1 - half);
+        c = c > half ? c : half;
+        r.lo = (c - half) > 0 ? (c - half) : 0;
+        r.hi = (c + half) < (L - 1) ? (c + half) : (L - 1);
+    }
+    return r;
+}
+
+// Per query tile along one axis: how many key tiles are fully kept by every query of the tile, and how many
+// are touched by at least one.
+void axis_census(int mask_kind, int L, int T, int W, int64_t *full, int64_t *touched)
+{
+    const int n = L / T;
+    for (int i = 0; i < n; ++i) {
+        int64_t f = 0, e = 0;
+        for (int j = 0; j < n; ++j) {
+            const int y0 = j * T, y1 = j * T + T - 1;
+            bool all = true, any = false;
+            for (int x = i * T; x < i * T + T; ++x) {
+                const TokenRange r = kept_token_range(mask_kind, L, T, W, x);
+                all = all && (r.lo <= y0 && y1 <= r.hi);
+                any = any || (r.lo <= y1 && y0 <= r.hi);
+            }
+            f += all;
+            e += any;
+        }
+        full[i] = f;
+        touched[i] = e;
+    }
 }
 
 }  // namespace
@@ -347,6 +399,48 @@ int sta_dump_key_tiles(int H, const int grid[3], const int tile[3], const int *w
         if (sta::launch_dump_key_tiles(p, win, dev_counts, dev_lists, static_cast<hipStream_t>(hip_stream)) !=
             hipSuccess)
             return STA_ERR_HIP;
+    }
+    return STA_OK;
+}
+
+int sta_block_census(int mask_kind, const int grid[3], const int tile[3], const int window_tokens[3],
+                     int64_t *dense_per_q, int64_t *mixed_per_q, int64_t totals[3])
+{
+    if (!window_tokens) return STA_ERR_NULL;
+    Shape s;
+    if (int rc = check_shape(1, 1, 8, grid, tile, &s)) return rc;
+    if (mask_kind != STA_MASK_STA && mask_kind != STA_MASK_NATTEN) return STA_ERR_UNSUPPORTED;
+    for (int a = 0; a < 3; ++a) {
+        if (window_tokens[a] < 1) return STA_ERR_WINDOW;
+        if (mask_kind == STA_MASK_STA && window_tokens[a] / tile[a] < 1) return STA_ERR_WINDOW;
+    }
+    int64_t *full[3], *touched[3];
+    int64_t *buf = new (std::nothrow) int64_t[2 * (size_t)(s.n[0] + s.n[1] + s.n[2])];
+    if (!buf) return STA_ERR_SHAPE;
+    int64_t *cur = buf;
+    for (int a = 0; a < 3; ++a) {
+        full[a] = cur;
+        touched[a] = cur + s.n[a];
+        cur += 2 * s.n[a];
+        axis_census(mask_kind, grid[a], tile[a], window_tokens[a], full[a], touched[a]);
+    }
+    int64_t dense_total = 0, mixed_total = 0;
+    int64_t q = 0;
+    for (int it = 0; it < s.n[0]; ++it)
+        for (int ih = 0; ih < s.n[1]; ++ih)
+            for (int iw = 0; iw < s.n[2]; ++iw, ++q) {
+                const int64_t dense = full[0][it] * full[1][ih] * full[2][iw];
+                const int64_t mixed = touched[0][it] * touched[1][ih] * touched[2][iw] - dense;
+                if (dense_per_q) dense_per_q[q] = dense;
+                if (mixed_per_q) mixed_per_q[q] = mixed;
+                dense_total += dense;
+                mixed_total += mixed;
+            }
+    delete[] buf;
+    if (totals) {
+        totals[0] = dense_total;
+        totals[1] = mixed_total;
+        totals[2] = s.n_tiles * s.n_tiles - dense_total - mixed_total;
     }
     return STA_OK;
 }

@@ -106,3 +106,50 @@ def test_error_returns_before_any_launch():
     assert lib.sta_key_tile_box(I3(2, 2, 2), I3(1, 1, 1), I3(0, 0, 2), lo, hi) == 2
     assert lib.sta_key_tile_box(I3(2, 2, 2), I3(1, 0, 1), I3(0, 0, 1), lo, hi) == 3
     assert sta.sta_workspace_bytes(1, 24, 128, (30, 48, 80), (6, 8, 8)) == 0
+
+
+@pytest.mark.parametrize("grid,tile,win", [
+    ((1, 24, 24), (1, 4, 4), (1, 12, 12)),
+    ((1, 24, 24), (1, 4, 4), (1, 11, 11)),
+    ((6, 8, 8), (2, 2, 2), (2, 6, 6)),
+    ((4, 6, 9), (2, 3, 3), (7, 5, 3)),
+    ((6, 6, 6), (1, 2, 3), (4, 4, 6)),
+    ((2, 3, 4), (1, 1, 2), (9, 9, 9)),
+    ((12, 12, 12), (4, 4, 4), (11, 11, 11)),
+])
+def test_block_census_matches_brute_force(grid, tile, win):
+    """The library counts blocks from per-axis interval tests; the oracle enumerates every token pair."""
+    for kind, name in ((sta.STA_MASK_STA, "sta"), (sta.STA_MASK_NATTEN, "natten")):
+        if name == "sta" and any(w // t < 1 for w, t in zip(win, tile)):
+            continue
+        dense, mixed, totals = sta.sta_block_census(kind, grid, tile, win)
+        o_dense, o_mixed = orc.block_census_per_query(name, "tiled", grid, tile, win)
+        assert dense == o_dense.tolist() and mixed == o_mixed.tolist()
+        n = len(dense)
+        assert totals == (o_dense.sum(), o_mixed.sum(), n * n - o_dense.sum() - o_mixed.sum())
+
+
+def test_block_census_table1_at_full_size():
+    """Table 1 at its own size (video 48^3, tile 4^3): STA windows 12^3 and 20^3 give 27 and 125 dense blocks for
+    every query tile and none mixed; the tiled sliding window 11^3 gives 1 dense and 124 mixed in the interior."""
+    grid, tile = (48, 48, 48), (4, 4, 4)
+    for w, per_q in ((12, 27), (20, 125)):
+        dense, mixed, totals = sta.sta_block_census(sta.STA_MASK_STA, grid, tile, (w, w, w))
+        assert set(dense) == {per_q} and set(mixed) == {0}
+        assert abs(100.0 * totals[0] / 1728 ** 2 - {12: 1.56, 20: 7.23}[w]) < 0.005
+    dense, mixed, totals = sta.sta_block_census(sta.STA_MASK_NATTEN, grid, tile, (11, 11, 11))
+    mid = (6 * 12 + 6) * 12 + 6
+    assert (dense[mid], mixed[mid]) == (1, 124)
+    assert totals[0] + totals[1] + totals[2] == 1728 ** 2
+
+
+def test_block_census_errors():
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_block_census(sta.STA_MASK_STA, (4, 4, 4), (2, 2, 2), (1, 2, 2))      # less than one tile
+    assert e.value.status == 3
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_block_census(sta.STA_MASK_NATTEN, (4, 4, 5), (2, 2, 2), (3, 3, 3))   # grid not a multiple
+    assert e.value.status == 2
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_block_census(7, (4, 4, 4), (2, 2, 2), (3, 3, 3))
+    assert e.value.status == 4

@@ -416,3 +416,70 @@ def test_mask_search_losses_match_dense_library_attention():
         local[idx] = _dense_softmax_attention(q[0, 0][idx], k[0, 0][idx], v[0, 0][idx], 0.5)
     np.testing.assert_allclose(losses[0, 0], ((full - local) ** 2).mean(), rtol=1e-12)
     assert best[0] == 0
+
+
+# ---- sliding-window (NATTEN) mask and the block census -------------------------------------------------------
+
+def test_natten_mask_is_sta_mask_with_unit_tiles():
+    """With tile (1,1,1) the STA mask algorithm reduces, line by line, to the sliding-window one."""
+    grid = (3, 5, 6)
+    for win in ((1, 1, 1), (3, 3, 3), (3, 5, 1), (5, 3, 7), (9, 9, 9), (2, 4, 6)):
+        a_dense, a_mixed = orc.block_census_per_query("sta", "tiled", grid, (1, 1, 1), win)
+        b_dense, b_mixed = orc.block_census_per_query("natten", "tiled", grid, (1, 1, 1), win)
+        assert (a_dense == b_dense).all() and (a_mixed == 0).all() and (b_mixed == 0).all()
+    # and pair by pair on one window
+    coords = [np.unravel_index(i, grid) for i in range(int(np.prod(grid)))]
+    for q in coords[::7]:
+        for k in coords:
+            t = tuple(int(abs(max(min(q[a], grid[a] - 1 - 1), 1) - k[a]) <= 1) for a in range(3))
+            assert orc.natten_keep(q, k, grid, (3, 3, 3)) == bool(t[0] and t[1] and t[2])
+
+
+def test_natten_every_query_attends_to_a_constant_number_of_keys():
+    """Sec. 2.2: the window centre is shifted at the borders so that every query keeps the same number of keys."""
+    grid = (4, 6, 7)
+    for win in ((3, 3, 3), (1, 5, 3), (3, 5, 7), (9, 3, 5)):
+        dense, _ = orc.block_census_per_query("natten", "tiled", grid, (1, 1, 1), win)
+        expect = int(np.prod([min(grid[a], 2 * (win[a] // 2) + 1) for a in range(3)]))
+        assert (dense == expect).all()
+
+
+def test_theorem1_interior_counts_one_axis():
+    """Theorem 1 per axis: an interior query tile has max(2*floor((W+1)/(2T)) - 1, 0) dense blocks and
+    2*ceil((W-1)/(2T)) + 1 non-empty ones."""
+    for T in (2, 3, 4, 8):
+        for W in range(1, 4 * T + 4, 2):
+            n = 2 * (-(-(W - 1) // (2 * T)) + 2) + 1          # enough tiles that the middle one sees no border
+            dense, mixed = orc.block_census_per_query("natten", "tiled", (1, 1, n * T), (1, 1, T), (1, 1, W))
+            mid = n // 2
+            assert dense[mid] == max(2 * ((W + 1) // (2 * T)) - 1, 0), (T, W)
+            assert dense[mid] + mixed[mid] == 2 * (-(-(W - 1) // (2 * T))) + 1, (T, W)
+
+
+def test_table1_tiled_natten_row():
+    """Table 1, Tiled NATTEN, tile 4^3, window 11^3: one dense and 124 mixed blocks per interior query tile, i.e.
+    0.06 % and 7.17 % of the 12^3 key tiles of the 48^3 video."""
+    (w, dense_pct, mixed_pct), = _rows("table1_tiled_natten_block_ratios.txt")
+    w = int(w)
+    dense, mixed = orc.block_census_per_query("natten", "tiled", (28, 28, 28), (4, 4, 4), (w, w, w))
+    mid = (3 * 7 + 3) * 7 + 3                                   # tile (3,3,3) of the 7^3 tile grid
+    assert (dense[mid], mixed[mid]) == (1, 124)
+    n_tiles_48 = 12 ** 3
+    assert abs(100.0 * dense[mid] / n_tiles_48 - float(dense_pct)) < 0.005
+    assert abs(100.0 * mixed[mid] / n_tiles_48 - float(mixed_pct)) < 0.01
+    # border tiles keep fewer blocks, which is what "ignoring boundary effects" leaves out
+    assert mixed.sum() < 124 * mixed.size and dense.sum() >= dense.size
+
+
+def test_fig3_block_types_for_the_three_orderings():
+    """Fig. 3 (image 24x24, window 12x12, tile 4x4): the sliding window in raster order has only mixed blocks,
+    tiling the tokens turns some of them dense, STA has no mixed block at all."""
+    grid, tile, win = (1, 24, 24), (1, 4, 4), (1, 12, 12)
+    rd, rm = orc.block_census_per_query("natten", "raster", grid, tile, win)
+    td, tm = orc.block_census_per_query("natten", "tiled", grid, tile, win)
+    sd, sm = orc.block_census_per_query("sta", "tiled", grid, tile, win)
+    assert sm.sum() == 0 and sd.sum() == 36 * 9
+    assert 0 < tm.sum() < rm.sum()
+    assert td.sum() > rd.sum()
+    # old and new census agree on STA
+    assert orc.block_census(grid, tile, win)[:2] == (sd.sum(), 0)
