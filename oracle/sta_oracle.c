@@ -19,6 +19,12 @@
  *                           keys (brute force), fp64 arithmetic.
  *   - sta_oracle_attention_lse: the same plus log(sum_j exp(S_ij + M_ij)) per row.
  *   - sta_oracle_probs:     one row of A (for the "rows sum to 1" invariant).
+ *   - sta_oracle_attention_backward: gradients of Eq. 1 with the same mask
+ *                           with respect to Q, K and V for a given upstream
+ *                           gradient of O (what finetuning through STA,
+ *                           Sec. 3.2, differentiates).  The paper prints no
+ *                           backward formula; this is the chain rule applied
+ *                           to Eq. 1, step by step, in fp64.
  *   - sta_oracle_tile_order / _tile_permute / _untile:
  *                           the tile-contiguous token order of Sec. 3.1
  *                           ("tokens within the same tile have consecutive
@@ -181,6 +187,138 @@ int sta_oracle_attention(const float *q, const float *k, const float *v,
                          double *out)
 {
     return sta_oracle_attention_lse(q, k, v, d, L, T, W, scale, query_idx, nq, out, NULL);
+}
+
+/* ---------------------------------------------------------------------- */
+/* Gradients of Eq. 1 (same mask) for ONE head, raster order.               */
+/* Forward:  S = Q K^T * scale,  A = softmax(S + M) row-wise,  O = A V.      */
+/* Given G = dLoss/dO, the chain rule gives, for kept pairs (i, j):         */
+/*   dV_j  = sum_i A_ij G_i                       (O is linear in V)        */
+/*   dA_ij = G_i . V_j                                                      */
+/*   dS_ij = A_ij (dA_ij - sum_l A_il dA_il)      (softmax Jacobian)        */
+/*         = A_ij (dA_ij - G_i . O_i)                                       */
+/*   dQ_i  = scale * sum_j dS_ij K_j,   dK_j = scale * sum_i dS_ij Q_i.     */
+/* Masked pairs have A_ij = 0 and contribute nothing.                       */
+/* dq is returned for the rows in query_idx, dk and dv for the rows in      */
+/* key_idx (each still summed over ALL partners by brute force).            */
+/* ---------------------------------------------------------------------- */
+int sta_oracle_attention_backward(const float *q, const float *k, const float *v,
+                                  const float *g, int d, const int L[3],
+                                  const int T[3], const int W[3], double scale,
+                                  const int64_t *query_idx, long nq,
+                                  const int64_t *key_idx, long nk,
+                                  double *dq, double *dk, double *dv)
+{
+    long N = (long)L[0] * L[1] * L[2];
+    /* Row statistics are needed for the queries asked for and for every query
+     * that keeps one of the keys asked for. */
+    unsigned char *need = (unsigned char *)calloc((size_t)N, 1);
+    double *row_max = (double *)malloc(sizeof(double) * (size_t)N);
+    double *row_den = (double *)malloc(sizeof(double) * (size_t)N);
+    double *row_go = (double *)malloc(sizeof(double) * (size_t)N);   /* G_i . O_i */
+    if (!need || !row_max || !row_den || !row_go) {
+        free(need); free(row_max); free(row_den); free(row_go);
+        return -1;
+    }
+    for (long n = 0; n < nq; ++n) need[query_idx[n]] = 1;
+#pragma omp parallel for schedule(static)
+    for (long i = 0; i < N; ++i) {
+        int qc[3], kc[3];
+        unravel(i, L, qc);
+        for (long n = 0; n < nk && !need[i]; ++n) {
+            unravel((long)key_idx[n], L, kc);
+            if (sta_oracle_keep(qc, kc, L, W, T)) need[i] = 1;
+        }
+    }
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *srow = (double *)malloc(sizeof(double) * (size_t)N);
+        double *orow = (double *)malloc(sizeof(double) * (size_t)d);
+        if (!srow || !orow) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp barrier
+        if (!failed) {
+            /* forward rows: max, denominator, G_i . O_i */
+#pragma omp for schedule(dynamic, 4)
+            for (long i = 0; i < N; ++i) {
+                if (!need[i]) continue;
+                int qc[3], kc[3];
+                unravel(i, L, qc);
+                double m = -INFINITY;
+                for (long j = 0; j < N; ++j) {
+                    unravel(j, L, kc);
+                    if (sta_oracle_keep(qc, kc, L, W, T)) {
+                        double dot = 0.0;
+                        for (int c = 0; c < d; ++c) dot += (double)q[i * d + c] * (double)k[j * d + c];
+                        srow[j] = dot * scale;
+                        if (srow[j] > m) m = srow[j];
+                    } else {
+                        srow[j] = -INFINITY;
+                    }
+                }
+                double den = 0.0;
+                for (long j = 0; j < N; ++j) den += exp(srow[j] - m);
+                for (int c = 0; c < d; ++c) orow[c] = 0.0;
+                for (long j = 0; j < N; ++j) {
+                    if (srow[j] == -INFINITY) continue;
+                    double a = exp(srow[j] - m) / den;
+                    for (int c = 0; c < d; ++c) orow[c] += a * (double)v[j * d + c];
+                }
+                double go = 0.0;
+                for (int c = 0; c < d; ++c) go += (double)g[i * d + c] * orow[c];
+                row_max[i] = m; row_den[i] = den; row_go[i] = go;
+            }
+            /* dQ rows */
+#pragma omp for schedule(dynamic, 4)
+            for (long n = 0; n < nq; ++n) {
+                long i = (long)query_idx[n];
+                int qc[3], kc[3];
+                unravel(i, L, qc);
+                for (int c = 0; c < d; ++c) dq[n * d + c] = 0.0;
+                for (long j = 0; j < N; ++j) {
+                    unravel(j, L, kc);
+                    if (!sta_oracle_keep(qc, kc, L, W, T)) continue;
+                    double dot = 0.0, da = 0.0;
+                    for (int c = 0; c < d; ++c) {
+                        dot += (double)q[i * d + c] * (double)k[j * d + c];
+                        da += (double)g[i * d + c] * (double)v[j * d + c];
+                    }
+                    double a = exp(dot * scale - row_max[i]) / row_den[i];
+                    double ds = a * (da - row_go[i]);
+                    for (int c = 0; c < d; ++c) dq[n * d + c] += scale * ds * (double)k[j * d + c];
+                }
+            }
+            /* dK and dV rows */
+#pragma omp for schedule(dynamic, 1)
+            for (long n = 0; n < nk; ++n) {
+                long j = (long)key_idx[n];
+                int qc[3], kc[3];
+                unravel(j, L, kc);
+                for (int c = 0; c < d; ++c) { dk[n * d + c] = 0.0; dv[n * d + c] = 0.0; }
+                for (long i = 0; i < N; ++i) {
+                    unravel(i, L, qc);
+                    if (!sta_oracle_keep(qc, kc, L, W, T)) continue;
+                    double dot = 0.0, da = 0.0;
+                    for (int c = 0; c < d; ++c) {
+                        dot += (double)q[i * d + c] * (double)k[j * d + c];
+                        da += (double)g[i * d + c] * (double)v[j * d + c];
+                    }
+                    double a = exp(dot * scale - row_max[i]) / row_den[i];
+                    double ds = a * (da - row_go[i]);
+                    for (int c = 0; c < d; ++c) {
+                        dv[n * d + c] += a * (double)g[i * d + c];
+                        dk[n * d + c] += scale * ds * (double)q[i * d + c];
+                    }
+                }
+            }
+        }
+        free(srow); free(orow);
+    }
+    free(need); free(row_max); free(row_den); free(row_go);
+    return failed ? -1 : 0;
 }
 
 /* One row of A (probabilities over all N keys) and its sum. */

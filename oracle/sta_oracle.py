@@ -53,6 +53,9 @@ def _load():
     lib.sta_oracle_block_census_per_query.argtypes = [c_int, c_int, _I3, _I3, _I3, c_void, c_void]
     lib.sta_oracle_block_census_per_query.restype = c_int
     lib.sta_oracle_num_threads.argtypes = []
+    lib.sta_oracle_attention_backward.argtypes = [c_void, c_void, c_void, c_void, c_int, _I3, _I3, _I3, c_double,
+                                                  c_void, c_long, c_void, c_long, c_void, c_void, c_void]
+    lib.sta_oracle_attention_backward.restype = c_int
     lib.sta_oracle_num_threads.restype = c_int
     _lib = lib
     return lib
@@ -108,6 +111,38 @@ def attention(q, k, v, grid, tile, window_tokens, scale=None, query_idx=None, re
     if rc != 0:
         raise MemoryError("oracle attention failed")
     return (out, lse) if return_lse else out
+
+
+def attention_backward(q, k, v, g, grid, tile, window_tokens, scale=None, query_idx=None, key_idx=None):
+    """Gradients of masked attention (Eq. 1) of ONE head with respect to q, k, v, given g = dLoss/dO.
+
+    q, k, v, g: [N, d] in raster order.  query_idx / key_idx: raster rows of dq / of dk and dv to return
+    (default: all).  Returns (dq [nq, d], dk [nk, d], dv [nk, d]) in fp64."""
+    lib = _load()
+    q, k, v, g = _f32(q), _f32(k), _f32(v), _f32(g)
+    N, d = q.shape
+    assert N == int(grid[0]) * int(grid[1]) * int(grid[2])
+    assert k.shape == (N, d) and v.shape == (N, d) and g.shape == (N, d)
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    if query_idx is None:
+        query_idx = np.arange(N, dtype=np.int64)
+    if key_idx is None:
+        key_idx = np.arange(N, dtype=np.int64)
+    query_idx = np.ascontiguousarray(query_idx, dtype=np.int64)
+    key_idx = np.ascontiguousarray(key_idx, dtype=np.int64)
+    for idx in (query_idx, key_idx):
+        assert idx.ndim == 1 and (idx >= 0).all() and (idx < N).all()
+    dq = np.empty((query_idx.shape[0], d), dtype=np.float64)
+    dk = np.empty((key_idx.shape[0], d), dtype=np.float64)
+    dv = np.empty((key_idx.shape[0], d), dtype=np.float64)
+    rc = lib.sta_oracle_attention_backward(q.ctypes.data, k.ctypes.data, v.ctypes.data, g.ctypes.data, d,
+                                           _i3(grid), _i3(tile), _i3(window_tokens), float(scale),
+                                           query_idx.ctypes.data, query_idx.shape[0], key_idx.ctypes.data,
+                                           key_idx.shape[0], dq.ctypes.data, dk.ctypes.data, dv.ctypes.data)
+    if rc != 0:
+        raise MemoryError("oracle backward failed")
+    return dq, dk, dv
 
 
 def attention_bh(q, k, v, grid, tile, window_tokens_per_head, scale=None, query_idx=None):

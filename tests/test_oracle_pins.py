@@ -483,3 +483,93 @@ def test_fig3_block_types_for_the_three_orderings():
     assert td.sum() > rd.sum()
     # old and new census agree on STA
     assert orc.block_census(grid, tile, win)[:2] == (sd.sum(), 0)
+
+
+# ---- gradients of Eq. 1 under the STA mask ---------------------------------------------------------------
+
+def _autograd_dense(q, k, v, g, scale, additive_mask=None):
+    """Library automatic differentiation of softmax(QK^T*scale + mask)V in fp64."""
+    import torch
+    tq, tk, tv = [torch.tensor(np.asarray(x, dtype=np.float64), requires_grad=True) for x in (q, k, v)]
+    s = tq @ tk.T * scale
+    if additive_mask is not None:
+        s = s + torch.tensor(additive_mask)
+    o = torch.softmax(s, dim=-1) @ tv
+    (o * torch.tensor(np.asarray(g, dtype=np.float64))).sum().backward()
+    return tq.grad.numpy(), tk.grad.numpy(), tv.grad.numpy()
+
+
+def test_backward_full_window_matches_library_autodiff():
+    grid, tile = (2, 4, 6), (1, 2, 2)
+    N, d = 48, 8
+    q, k, v, g = (_rand((N, d), s) for s in (61, 62, 63, 64))
+    dq, dk, dv = orc.attention_backward(q, k, v, g, grid, tile, grid, scale=0.3)
+    for mine, ref in zip((dq, dk, dv), _autograd_dense(q, k, v, g, 0.3)):
+        np.testing.assert_allclose(mine, ref, rtol=0, atol=1e-13)
+
+
+def test_backward_unit_window_is_per_tile_dense_autodiff():
+    grid, tile = (2, 4, 4), (1, 2, 2)
+    N, d = 32, 4
+    q, k, v, g = (_rand((N, d), s) for s in (65, 66, 67, 68))
+    dq, dk, dv = orc.attention_backward(q, k, v, g, grid, tile, tile)
+    coords = np.stack(np.unravel_index(np.arange(N), grid), axis=1)
+    tid = np.ravel_multi_index((coords // np.array(tile)).T, (2, 2, 2))
+    for t in range(8):
+        idx = np.nonzero(tid == t)[0]
+        refs = _autograd_dense(q[idx], k[idx], v[idx], g[idx], 0.5)
+        for mine, ref in zip((dq, dk, dv), refs):
+            np.testing.assert_allclose(mine[idx], ref, rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("win", [(1, 6, 2), (2, 2, 6), (1, 2, 2)])
+def test_backward_windowed_matches_finite_differences_of_the_forward(win):
+    """Central differences of sum(O * G) computed with the (separately pinned) forward oracle."""
+    grid, tile = (2, 4, 6), (1, 2, 2)
+    N, d = 48, 8
+    q, k, v, g = (_rand((N, d), s) for s in (71, 72, 73, 74))
+    dq, dk, dv = orc.attention_backward(q, k, v, g, grid, tile, win)
+
+    def loss(qq, kk, vv):
+        return float((orc.attention(qq, kk, vv, grid, tile, win) * g).sum())
+
+    eps = 2.0 ** -10                                            # exactly representable steps
+    for which, grad in enumerate((dq, dk, dv)):
+        for (i, c) in ((0, 0), (17, 3), (30, 5), (47, 7)):
+            args_p, args_m = [q.copy(), k.copy(), v.copy()], [q.copy(), k.copy(), v.copy()]
+            args_p[which][i, c] += eps
+            args_m[which][i, c] -= eps
+            fd = (loss(*args_p) - loss(*args_m)) / (float(args_p[which][i, c]) - float(args_m[which][i, c]))
+            assert abs(fd - grad[i, c]) <= 2e-6 * max(1.0, abs(fd)), (which, i, c, fd, grad[i, c])
+
+
+def test_backward_windowed_matches_library_autodiff_with_additive_mask():
+    """The mask enters Eq. 1 as M (0 / -inf added to S): hand that matrix to the library's autodiff."""
+    grid, tile, win = (2, 6, 6), (1, 2, 3), (1, 6, 3)           # even tile-window along h, borders on every axis
+    N, d = 72, 8
+    q, k, v, g = (_rand((N, d), s) for s in (75, 76, 77, 78))
+    coords = [tuple(int(x) for x in np.unravel_index(i, grid)) for i in range(N)]
+    M = np.array([[0.0 if orc.keep(qi, kj, grid, win, tile) else -np.inf for kj in coords] for qi in coords])
+    dq, dk, dv = orc.attention_backward(q, k, v, g, grid, tile, win)
+    for mine, ref in zip((dq, dk, dv), _autograd_dense(q, k, v, g, 1.0 / np.sqrt(d), M)):
+        np.testing.assert_allclose(mine, ref, rtol=0, atol=1e-13)
+    # a sample of rows gives the same rows
+    qi, ki = np.array([3, 40, 71]), np.array([0, 35])
+    sq, sk, sv = orc.attention_backward(q, k, v, g, grid, tile, win, query_idx=qi, key_idx=ki)
+    np.testing.assert_array_equal(sq, dq[qi])
+    np.testing.assert_array_equal(sk, dk[ki])
+    np.testing.assert_array_equal(sv, dv[ki])
+
+
+def test_backward_invariants():
+    grid, tile, win = (2, 4, 6), (1, 2, 2), (1, 6, 2)
+    N, d = 48, 8
+    q, k, v, g = (_rand((N, d), s) for s in (81, 82, 83, 84))
+    dq, dk, dv = orc.attention_backward(q, k, v, g, grid, tile, win)
+    # adding one vector to every key shifts each score row by a constant: the loss does not move
+    assert np.abs(dk.sum(axis=0)).max() < 1e-13
+    # O is a convex combination of V rows: shifting all of V by c shifts O by c, so sum_j dV_j = sum_i G_i
+    np.testing.assert_allclose(dv.sum(axis=0), g.astype(np.float64).sum(axis=0), atol=1e-13)
+    # constant V: O does not depend on Q or K
+    dq0, dk0, _ = orc.attention_backward(q, k, np.ones_like(v), g, grid, tile, win)
+    assert np.abs(dq0).max() < 1e-13 and np.abs(dk0).max() < 1e-13
