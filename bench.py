@@ -54,7 +54,10 @@ def parse_args():
     ap.add_argument("--extras", action="store_true",
                     help="instead of the benchmark line, time the entry points built on top of the attention kernel "
                          "(log-denominator output, recall, per-head MSE, mask search) on the workload, one JSON line")
-    ap.add_argument("--profile-only", default=None, choices=[None, "forward", "permute", "layer", "copy"],
+    ap.add_argument("--backward", action="store_true",
+                    help="instead of the benchmark line, time the gradient entry point (sta_backward) on the workload, "
+                         "one JSON line")
+    ap.add_argument("--profile-only", default=None, choices=[None, "forward", "permute", "layer", "copy", "backward"],
                     help="run only this part (for rocprofv3), print nothing else; 'copy' is a plain "
                          "device copy of one tensor, the known-size reference for the traffic counters")
     return ap.parse_args()
@@ -217,8 +220,35 @@ def main():
         }))
         return
 
+    bwd = None
+    if args.backward or args.profile_only == "backward":
+        layer.permute_in()
+        lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=device)
+        sta.sta_forward_lse(layer.qt, layer.kt, layer.vt, layer.ot, lse, w.grid, w.tile, w.window_tiles)
+        d_o = layer.q                                   # any N(0,1) bf16 tensor of the right shape serves as dO
+        d_q, d_k, d_v = layer.k, layer.v, layer.o       # raster inputs are no longer needed: reuse as outputs
+        bws = torch.empty(sta.sta_backward_workspace_bytes(w.B, w.H, w.grid), dtype=torch.uint8, device=device)
+        bwd = lambda: sta.sta_backward(layer.qt, layer.kt, layer.vt, layer.ot, d_o, lse, d_q, d_k, d_v, w.grid, w.tile,
+                                       w.window_tiles, bws)
+    if args.backward:
+        ms = event_time_ms(bwd, max(args.steps // 4, 2), warmup=1)
+        torch.cuda.synchronize()
+        pairs_flops = sta.sta_kept_flops(w.B, w.H, w.D, w.grid, w.tile, w.window_tiles)     # 4*P^2*D per kept pair
+        print(json.dumps({
+            "backward": "%s: B=%d H=%d D=%d grid=%s tile=%s" % (w.name, w.B, w.H, w.D, w.grid, w.tile),
+            "sta_backward_ms": ms,
+            "products_needed": 5, "products_executed": 7,
+            "tflops_needed": 2.5 * pairs_flops / (ms * 1e-3) / 1e12,
+            "tflops_executed": 3.5 * pairs_flops / (ms * 1e-3) / 1e12,
+            "frac_of_peak_needed": 2.5 * pairs_flops / (ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
+            "frac_of_peak_executed": 3.5 * pairs_flops / (ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
+            "note": "S and dP are computed in both the dQ kernel and the dK/dV kernel (7 matrix products per kept "
+                    "block against the 5 the chain rule needs); the forward pass is not included",
+        }))
+        return
+
     if args.profile_only:
-        fn = {"forward": layer.forward, "permute": lambda: (layer.permute_in(), layer.untile()),
+        fn = {"backward": bwd, "forward": layer.forward, "permute": lambda: (layer.permute_in(), layer.untile()),
               "layer": layer.step, "copy": lambda: layer.qt.copy_(layer.q)}[args.profile_only]
         layer.permute_in()
         for _ in range(args.warmup + args.steps):

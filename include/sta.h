@@ -97,6 +97,35 @@ int sta_forward_lse(const void *q_tiled, const void *k_tiled, const void *v_tile
                     float scale, void *hip_stream);
 
 /*
+ * Gradients of sta_forward (what finetuning through STA layers, Sec. 3.2, differentiates): the chain
+ * rule of Eq. 1 under the same mask.  With P = softmax(S + M) row-wise and dO the gradient of the
+ * loss with respect to O:  dV = P^T dO,  dP = dO V^T,  dS = P o (dP - rowsum(dO o O)),
+ * dQ = dS K * scale,  dK = dS^T Q * scale, summed over kept (query tile, key tile) pairs only.
+ * q/k/v/o/d_o: device, bf16, [B, H, N, D] in TILED order, o and lse_tiled as returned by
+ * sta_forward_lse for the same q, k, v, windows and scale.  d_q/d_k/d_v: device, bf16, same shape,
+ * written; they must not overlap any input or each other.  Arithmetic: P is recomputed from the
+ * scores and lse in fp32, P and dS are rounded to bf16 for the matrix products, accumulation in
+ * fp32, results rounded to bf16.  No atomics: repeated calls give identical bits.
+ * workspace: device, 16-byte aligned, at least sta_backward_workspace_bytes(B, H, grid) bytes
+ * (one float per query row), else STA_ERR_WORKSPACE.
+ * Supported: D = 128 and P a multiple of 128; anything else returns STA_ERR_UNSUPPORTED.
+ */
+size_t sta_backward_workspace_bytes(int B, int H, const int grid[3]);
+int sta_backward(const void *q_tiled, const void *k_tiled, const void *v_tiled,
+                 const void *o_tiled, const void *d_o_tiled, const float *lse_tiled,
+                 void *d_q_tiled, void *d_k_tiled, void *d_v_tiled, int B, int H, int D,
+                 const int grid[3], const int tile[3], const int *window_tiles, float scale,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Query-tile box of one key tile: the query tiles whose window (sta_key_tile_box) contains key tile
+ * k_tile.  It is the set the gradient kernels walk per key tile; at the borders it is not the mirror
+ * image of the key-tile box.  Host, pure integer, inclusive bounds.
+ */
+int sta_query_tile_box(const int grid_tiles[3], const int window_tiles[3],
+                       const int k_tile[3], int lo[3], int hi[3]);
+
+/*
  * Per-head mean squared error between two attention outputs, the loss of the
  * paper's mask-search algorithm ("STA Mask Search": loss <- MSE(O, O')).
  * a, b: device, bf16, [B, H, N, D] in the same token order.  dev_mse: device,

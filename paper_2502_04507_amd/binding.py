@@ -19,6 +19,7 @@ EXPORTED_SYMBOLS = (
     "sta_tile_permute", "sta_untile", "sta_forward", "sta_forward_lse", "sta_workspace_bytes", "sta_key_tile_box",
     "sta_dump_key_tiles", "sta_window_tokens_to_tiles", "sta_kept_flops", "sta_strerror", "sta_version",
     "sta_head_mse_workspace_bytes", "sta_head_mse", "sta_mask_search", "sta_attention_recall", "sta_block_census",
+    "sta_backward_workspace_bytes", "sta_backward", "sta_query_tile_box",
 )
 
 
@@ -71,6 +72,14 @@ def load_library():
     lib.sta_window_tokens_to_tiles.restype = ci
     lib.sta_kept_flops.argtypes = [ci, ci, ci, _I3, _I3, ctypes.POINTER(ci)]
     lib.sta_kept_flops.restype = ctypes.c_double
+    vp = ctypes.c_void_p
+    lib.sta_backward_workspace_bytes.argtypes = [ci, ci, _I3]
+    lib.sta_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.sta_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, _I3, _I3, ctypes.POINTER(ci),
+                                 ctypes.c_float, vp, ctypes.c_size_t, vp]
+    lib.sta_backward.restype = ci
+    lib.sta_query_tile_box.argtypes = [_I3, _I3, _I3, _I3, _I3]
+    lib.sta_query_tile_box.restype = ci
     lib.sta_block_census.argtypes = [ci, _I3, _I3, _I3, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.sta_block_census.restype = ci
     lib.sta_strerror.argtypes = [ci]
@@ -190,6 +199,38 @@ def sta_forward_lse(q_tiled, k_tiled, v_tiled, o_tiled, lse_tiled, grid, tile, w
                                _dev(lse_tiled, "lse"), B, H, D, _i3(grid), _i3(tile), _windows(window_tiles, H),
                                float(scale), _stream_ptr(stream)))
     return o_tiled, lse_tiled
+
+
+def sta_backward_workspace_bytes(B, H, grid) -> int:
+    return int(load_library().sta_backward_workspace_bytes(int(B), int(H), _i3(grid)))
+
+
+def sta_backward(q_tiled, k_tiled, v_tiled, o_tiled, d_o_tiled, lse_tiled, d_q_tiled, d_k_tiled, d_v_tiled, grid, tile,
+                 window_tiles, workspace, scale=0.0, stream=None):
+    """Gradients of sta_forward.  All tensors bf16 [B,H,N,D] in tiled order except lse_tiled (float32 [B,H,N]) and
+    workspace (any dtype, at least sta_backward_workspace_bytes bytes)."""
+    lib = load_library()
+    for t in (q_tiled, k_tiled, v_tiled, o_tiled, d_o_tiled, d_q_tiled, d_k_tiled, d_v_tiled):
+        if t.dim() != 4 or t.shape != q_tiled.shape or t.dtype != torch.bfloat16:
+            raise ValueError("expect bf16 [B, H, N, D] tensors of equal shape")
+    B, H, N, D = q_tiled.shape
+    if lse_tiled.dtype != torch.float32 or tuple(lse_tiled.shape) != (B, H, N):
+        raise ValueError("lse_tiled must be float32 [B, H, N]")
+    if N != int(grid[0]) * int(grid[1]) * int(grid[2]):
+        raise ValueError("N does not match the grid")
+    _check(lib.sta_backward(_dev(q_tiled, "q"), _dev(k_tiled, "k"), _dev(v_tiled, "v"), _dev(o_tiled, "o"),
+                            _dev(d_o_tiled, "d_o"), _dev(lse_tiled, "lse"), _dev(d_q_tiled, "d_q"),
+                            _dev(d_k_tiled, "d_k"), _dev(d_v_tiled, "d_v"), B, H, D, _i3(grid), _i3(tile),
+                            _windows(window_tiles, H), float(scale), _dev(workspace, "workspace"),
+                            workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+    return d_q_tiled, d_k_tiled, d_v_tiled
+
+
+def sta_query_tile_box(grid_tiles, window_tiles, k_tile):
+    """Host-side, pure integer: inclusive (lo, hi) box of the query tiles that keep key tile k_tile."""
+    lo, hi = _I3(), _I3()
+    _check(load_library().sta_query_tile_box(_i3(grid_tiles), _i3(window_tiles), _i3(k_tile), lo, hi))
+    return tuple(lo), tuple(hi)
 
 
 def sta_key_tile_box(grid_tiles, window_tiles, q_tile):

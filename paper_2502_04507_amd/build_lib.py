@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libsta.so")
 BUILD_DIR = os.path.join(HERE, "_build")
-SOURCES = ["sta_api.hip", "sta_permute.hip", "sta_attention.hip", "sta_reduce.hip"]
+SOURCES = ["sta_api.hip", "sta_permute.hip", "sta_attention.hip", "sta_reduce.hip", "sta_backward.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

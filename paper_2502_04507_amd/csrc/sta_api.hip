@@ -382,6 +382,78 @@ int sta_key_tile_box(const int grid_tiles[3], const int window_tiles[3], const i
     return STA_OK;
 }
 
+int sta_query_tile_box(const int grid_tiles[3], const int window_tiles[3], const int k_tile[3], int lo[3], int hi[3])
+{
+    if (!grid_tiles || !window_tiles || !k_tile || !lo || !hi) return STA_ERR_NULL;
+    for (int a = 0; a < 3; ++a) {
+        if (grid_tiles[a] <= 0 || k_tile[a] < 0 || k_tile[a] >= grid_tiles[a]) return STA_ERR_SHAPE;
+        if (window_tiles[a] < 1) return STA_ERR_WINDOW;
+    }
+    for (int a = 0; a < 3; ++a) {
+        const int n = grid_tiles[a];
+        const int w = window_tiles[a] < 2 * n ? window_tiles[a] : 2 * n;
+        const StaAxisRange r = sta_axis_query_range(n, w, k_tile[a]);
+        lo[a] = r.lo;
+        hi[a] = r.hi;
+    }
+    return STA_OK;
+}
+
+size_t sta_backward_workspace_bytes(int B, int H, const int grid[3])
+{
+    if (!grid || B <= 0 || H <= 0 || grid[0] <= 0 || grid[1] <= 0 || grid[2] <= 0) return 0;
+    return (size_t)B * H * (size_t)grid[0] * grid[1] * grid[2] * sizeof(float);
+}
+
+int sta_backward(const void *q_tiled, const void *k_tiled, const void *v_tiled, const void *o_tiled,
+                 const void *d_o_tiled, const float *lse_tiled, void *d_q_tiled, void *d_k_tiled, void *d_v_tiled, int B,
+                 int H, int D, const int grid[3], const int tile[3], const int *window_tiles, float scale,
+                 void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!q_tiled || !k_tiled || !v_tiled || !o_tiled || !d_o_tiled || !lse_tiled || !d_q_tiled || !d_k_tiled ||
+        !d_v_tiled)
+        return STA_ERR_NULL;
+    Shape s;
+    if (int rc = check_shape(B, H, D, grid, tile, &s)) return rc;
+    if (int rc = check_windows(H, window_tiles)) return rc;
+    if (!sta::backward_supported((int)s.P, D)) return STA_ERR_UNSUPPORTED;
+    const size_t bytes = (size_t)B * H * s.N * D * 2;
+    const size_t stat_bytes = (size_t)B * H * s.N * sizeof(float);
+    if (!workspace || workspace_bytes < stat_bytes || ((uintptr_t)workspace & 15) != 0) return STA_ERR_WORKSPACE;
+    if (((uintptr_t)lse_tiled & 15) != 0) return STA_ERR_SHAPE;
+    const void *inputs[5] = {q_tiled, k_tiled, v_tiled, o_tiled, d_o_tiled};
+    void *outputs[3] = {d_q_tiled, d_k_tiled, d_v_tiled};
+    for (int i = 0; i < 3; ++i) {
+        for (int j = 0; j < 5; ++j)
+            if (ranges_overlap(outputs[i], bytes, inputs[j], bytes)) return STA_ERR_ALIAS;
+        for (int j = i + 1; j < 3; ++j)
+            if (ranges_overlap(outputs[i], bytes, outputs[j], bytes)) return STA_ERR_ALIAS;
+        if (ranges_overlap(outputs[i], bytes, lse_tiled, stat_bytes) || ranges_overlap(outputs[i], bytes, workspace, stat_bytes))
+            return STA_ERR_ALIAS;
+    }
+    for (int j = 0; j < 5; ++j)
+        if (ranges_overlap(workspace, stat_bytes, inputs[j], bytes)) return STA_ERR_ALIAS;
+    if (ranges_overlap(workspace, stat_bytes, lse_tiled, stat_bytes)) return STA_ERR_ALIAS;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+    sta::FwdParams p = make_fwd_params(s, H, scale * 1.4426950408889634f);
+
+    int max_heads = sta::kMaxHeadsPerLaunch;
+    if ((int64_t)B * max_heads > 65535) max_heads = 65535 / B;
+    if (max_heads < 1) return STA_ERR_SHAPE;
+    for (int hb = 0; hb < H; hb += max_heads) {
+        const int heads = (H - hb) < max_heads ? (H - hb) : max_heads;
+        sta::WindowTable win;
+        fill_window_table(&win, window_tiles, hb, heads, s.n);
+        p.head_base = hb;
+        p.heads = heads;
+        hipError_t e = sta::launch_backward(q_tiled, k_tiled, v_tiled, o_tiled, d_o_tiled, lse_tiled,
+                                            static_cast<float *>(workspace), hb == 0, d_q_tiled, d_k_tiled, d_v_tiled, B,
+                                            p, win, static_cast<hipStream_t>(hip_stream));
+        if (e != hipSuccess) return STA_ERR_HIP;
+    }
+    return STA_OK;
+}
+
 int sta_dump_key_tiles(int H, const int grid[3], const int tile[3], const int *window_tiles, int32_t *dev_counts,
                        int32_t *dev_lists, void *hip_stream)
 {

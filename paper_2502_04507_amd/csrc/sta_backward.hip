@@ -1,0 +1,461 @@
+// Gradients of Sliding Tile Attention for gfx950 (MI355X): dQ, dK, dV of Eq. 1 under the STA mask, for the
+// finetuning use of the paper (Sec. 3.2 trains through STA layers).  The paper gives no backward kernel; this
+// is the chain rule of Eq. 1 evaluated block by block over the kept (query tile, key tile) pairs only:
+//
+//   P_ij  = exp(S_ij - lse_i)          S = Q K^T * scale, lse_i = ln sum_j exp(S_ij) from the forward pass
+//   dV_j  = sum_i P_ij dO_i
+//   dP_ij = dO_i . V_j
+//   dS_ij = P_ij (dP_ij - delta_i)     delta_i = dO_i . O_i
+//   dQ_i  = scale * sum_j dS_ij K_j    dK_j = scale * sum_i dS_ij Q_i
+//
+// Three kernels, no atomics, results repeatable:
+//   sta_bwd_delta_kernel  delta_i for every query row (HBM-bound, reads O and dO once);
+//   sta_bwd_dq_kernel     one workgroup per query block, walks the key tiles of its window (as the forward
+//                         kernel does): 3 MFMA products per block (K Q^T, V dO^T, K^T dS^T);
+//   sta_bwd_dkv_kernel    one workgroup per key block, walks the QUERY tiles that keep its key tile (the
+//                         transposed box): 4 MFMA products per block (Q K^T, dO V^T, dO^T P, Q^T dS).
+// S and dP are thus computed twice (7 products against the 5 of a single-pass scheme with atomics on dQ).
+//
+// Same MFMA formulation as the forward kernel: the block is held transposed so that one lane owns one column
+// (a query in the dQ kernel, a key in the dK/dV kernel), and the bf16-rounded P or dS goes from the
+// accumulators straight into the B operand of the next product, the contraction index being fed in
+// accumulator order.  Staged operands sit row-major in LDS (256 B per token), brought in by
+// global_load_lds; an operand that is read both by rows (A rows = tokens) and transposed (A rows = channels)
+// is staged twice, once with each of the two XOR swizzles that make the respective reads bank-conflict free.
+// Head dimension 128; tokens per tile a multiple of 128.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sta_device_util.h"
+#include "sta_geometry.h"
+#include "sta_internal.h"
+
+namespace {
+
+constexpr int kD = 128;
+constexpr int kRowB = kD * 2;          // bytes per token row
+constexpr int kSub = 32;               // tokens per staged sub-block
+constexpr int kTileB = kSub * kRowB;   // 8 KB: one staged operand
+constexpr int kNW = 4;                 // waves per workgroup, 32 columns each
+constexpr int kCols = kNW * 32;        // queries (dQ kernel) or keys (dK/dV kernel) per workgroup
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Byte offset, inside a row-major [32][128] bf16 sub-block in global memory, of the 16-byte chunk that belongs
+// at LDS slot `slot` (0..15) of row `row` under the row-read swizzle (c ^ (row & 15)) or the transposed-read
+// swizzle (c ^ ((row & 3) << 2)).
+__device__ __forceinline__ uint32_t src_chunk_offset(int row, int slot, bool transposed_read)
+{
+    const int chunk = transposed_read ? (slot ^ ((row & 3) << 2)) : (slot ^ (row & 15));
+    return (uint32_t)(row * kRowB + (chunk << 4));
+}
+
+// acc(32 x 32) = A B with A = a staged sub-block read by rows (A rows = its 32 tokens, k = channels) at byte
+// offset OFF of LDS, and B = eight resident fragments (k = channels).  Reads go out one group of four k-steps
+// ahead of the MFMAs that use them.
+template <int OFF>
+__device__ __forceinline__ floatx16 rows_times_resident(const uint32_t (&row_addr)[8], const bf16x8 (&resident)[8])
+{
+    floatx16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    bf16x8 frag[2][4];
+    k_issue<0, kRowB, OFF>(frag[0], row_addr);
+    k_issue<1, kRowB, OFF>(frag[1], row_addr);
+    k_wait<4>(frag[0]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc = mfma_32x32x16(frag[0][i], resident[i], acc);
+    __builtin_amdgcn_sched_barrier(0);
+    k_wait<0>(frag[1]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc = mfma_32x32x16(frag[1][i], resident[4 + i], acc);
+    __builtin_amdgcn_sched_barrier(0);
+    return acc;
+}
+
+// acc[db](32 channels x 32 columns) += A B with A = the staged sub-block at OFF read transposed (A rows =
+// channels, k = its 32 tokens in accumulator order) and B = the two packed halves of an accumulator.
+template <int OFF>
+__device__ __forceinline__ void transposed_times_packed(const uint32_t (&tr_addr)[4], const bf16x8 (&packed)[2],
+                                                        floatx16 (&acc)[4])
+{
+    typedef short shortx8 __attribute__((ext_vector_type(8)));
+    shortx4 frag[2][4][2];
+    pv_issue<OFF, 4, kRowB>(frag[0], tr_addr);
+    pv_issue<OFF + 16 * kRowB, 4, kRowB>(frag[1], tr_addr);
+    pv_wait<8>(frag[0]);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+        const shortx8 a = __builtin_shufflevector(frag[0][db][0], frag[0][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
+        acc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, a), packed[0], acc[db]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    pv_wait<0>(frag[1]);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+        const shortx8 a = __builtin_shufflevector(frag[1][db][0], frag[1][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
+        acc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, a), packed[1], acc[db]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+__device__ __forceinline__ void pack16(const float (&x)[16], bf16x8 (&out)[2])
+{
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[j][e] = static_cast<__bf16>(x[8 * j + e]);
+}
+
+// Walks the sub-blocks of the tiles of a box in ascending tile order; row() is the first token row (tiled
+// order, inside the head) of the sub-block to request next.
+struct BoxWalk {
+    StaBox box;
+    int n_h, n_w, P, sub_per_tile;
+    int t, h, w, s;
+    uint32_t next_row;
+    __device__ __forceinline__ void start(const StaBox &b, int nh, int nw, int tokens_per_tile)
+    {
+        box = b; n_h = nh; n_w = nw; P = tokens_per_tile; sub_per_tile = tokens_per_tile / kSub;
+        t = b.t.lo; h = b.h.lo; w = b.w.lo; s = 0;
+        next_row = tile_row();
+    }
+    __device__ __forceinline__ uint32_t tile_row() const { return (uint32_t)(((t * n_h + h) * n_w + w) * P); }
+    __device__ __forceinline__ void advance()
+    {
+        next_row += kSub;
+        if (++s == sub_per_tile) {
+            s = 0;
+            if (++w > box.w.hi) {
+                w = box.w.lo;
+                if (++h > box.h.hi) { h = box.h.lo; ++t; }
+                next_row = tile_row();
+            }
+        }
+    }
+};
+
+// Per-lane constants of the operand reads (relative to the start of a staged sub-block).
+__device__ __forceinline__ void operand_addresses(uint32_t smem_addr, int lane, uint32_t (&row_addr)[8],
+                                                  uint32_t (&tr_addr)[4])
+{
+    const int lo = lane & 31, hb = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) row_addr[ks] = smem_addr + (uint32_t)(lo * kRowB + (((2 * ks + hb) ^ (lo & 15)) << 4));
+    const int j4 = (lane & 15) >> 2, s4 = lane & 3, blk = (lane >> 4) & 1;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+        tr_addr[db] = smem_addr + (uint32_t)((4 * hb + j4) * kRowB + ((((db ^ j4) << 2) | (2 * blk + (s4 >> 1))) << 4) + 8 * (s4 & 1));
+}
+
+// Resident B-operand fragments of this wave's 32 columns (rows of x): column lo, channels 16*ks + 8*hb ..
+__device__ __forceinline__ void load_resident(const bf16_raw *rows, int lane, bf16x8 (&frag)[8])
+{
+    const int lo = lane & 31, hb = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) frag[ks] = *reinterpret_cast<const bf16x8 *>(rows + (size_t)lo * kD + ks * 16 + hb * 8);
+}
+
+// Stores the transposed accumulator (channels x 32 columns) times `mul` as bf16 rows of `dst`.
+__device__ __forceinline__ void store_columns(bf16_raw *dst, int lane, const floatx16 (&acc)[4], float mul)
+{
+    const int lo = lane & 31, hb = lane >> 5;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            bf16x4 ov;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ov[t] = static_cast<__bf16>(acc[db][4 * g + t] * mul);
+            *reinterpret_cast<bf16x4 *>(dst + (size_t)lo * kD + db * 32 + g * 8 + hb * 4) = ov;
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// delta_i = dO_i . O_i, one 16-lane group per row (each lane 16 bytes of the 256-byte row).
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void sta_bwd_delta_kernel(const uint4 *__restrict__ o, const uint4 *__restrict__ d_o,
+                                                            float *__restrict__ delta, size_t rows)
+{
+    const size_t row = (size_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int part = threadIdx.x & 15;
+    float acc = 0.f;
+    if (row < rows) {
+        const uint4 a = o[row * 16 + part], b = d_o[row * 16 + part];
+        const uint32_t as[4] = {a.x, a.y, a.z, a.w}, bs[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc = fmaf(__uint_as_float(as[e] << 16), __uint_as_float(bs[e] << 16), acc);
+            acc = fmaf(__uint_as_float(as[e] & 0xffff0000u), __uint_as_float(bs[e] & 0xffff0000u), acc);
+        }
+    }
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 16);
+    if (row < rows && part == 0) delta[row] = acc;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// dQ.  grid = (N / 128, B * heads).  LDS stage: K for row reads, K for transposed reads, V for row reads.
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw *__restrict__ q,
+                                                                 const bf16_raw *__restrict__ k,
+                                                                 const bf16_raw *__restrict__ v,
+                                                                 const bf16_raw *__restrict__ d_o,
+                                                                 const float *__restrict__ lse,
+                                                                 const float *__restrict__ delta,
+                                                                 bf16_raw *__restrict__ d_q, sta::FwdParams p,
+                                                                 sta::WindowTable win)
+{
+    constexpr int OPS = 3, STAGE_B = OPS * kTileB;
+    constexpr int K_ROWS = 0, K_TR = kTileB, V_ROWS = 2 * kTileB;
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
+
+    const uint32_t qblock = blockIdx.x;
+    const uint32_t heads = p.heads;
+    const uint32_t h_local = blockIdx.y % heads, b = blockIdx.y / heads;
+    const size_t bh = (size_t)b * p.H + p.head_base + h_local;
+    const uint32_t q_tile = (qblock * kCols) / p.P;
+    const StaBox box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1], win.w[h_local][2],
+                                           q_tile);
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, lo = lane & 31;
+
+    const size_t my_row = bh * p.N + (size_t)qblock * kCols + (size_t)wave * 32;
+    const char *kh = reinterpret_cast<const char *>(k + bh * p.N * kD);
+    const char *vh = reinterpret_cast<const char *>(v + bh * p.N * kD);
+
+    // DMA: each operand is 8 instructions of 1 KB (4 rows); wave w issues instructions 2w and 2w+1 of each.
+    uint32_t off_rows[2], off_tr[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = 4 * (2 * wave + i) + (lane >> 4);
+        off_rows[i] = src_chunk_offset(row, lane & 15, false);
+        off_tr[i] = src_chunk_offset(row, lane & 15, true);
+    }
+    auto issue_loads = [&](int stage, uint32_t first_row) {
+        const size_t base = (size_t)first_row * kRowB;
+        char *dst = smem + stage * STAGE_B + (2 * wave) * 1024;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + base + off_rows[i]),
+                                             STA_LDS_PTR(dst + K_ROWS + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + base + off_tr[i]),
+                                             STA_LDS_PTR(dst + K_TR + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + base + off_rows[i]),
+                                             STA_LDS_PTR(dst + V_ROWS + i * 1024), 16, 0, 0);
+        }
+    };
+
+    uint32_t row_addr[8], tr_addr[4];
+    operand_addresses((uint32_t)(uintptr_t)smem, lane, row_addr, tr_addr);
+
+    bf16x8 Qr[8], Gr[8];
+    load_resident(q + my_row * kD, lane, Qr);
+    load_resident(d_o + my_row * kD, lane, Gr);
+    const float c = p.scale_log2e;
+    const float lse2 = lse[my_row + lo] * kLog2e;
+    const float dl = delta[my_row + lo];
+
+    floatx16 dQ[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dQ[db][r] = 0.f;
+
+    BoxWalk walk;
+    walk.start(box, p.n_h, p.n_w, p.P);
+    const int n_iter = box.count() * walk.sub_per_tile;
+    int issued = 0;
+    auto issue_next = [&]() {
+        if (issued < n_iter) {
+            issue_loads(issued & 1, walk.next_row);
+            walk.advance();
+            ++issued;
+        }
+    };
+    issue_next();
+
+    auto sub_block = [&](auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value * STAGE_B;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        issue_next();
+        const floatx16 S = rows_times_resident<ST + K_ROWS>(row_addr, Qr);     // S^T  = K Q^T   (keys x queries)
+        const floatx16 dP = rows_times_resident<ST + V_ROWS>(row_addr, Gr);    // dP^T = V dO^T
+        float ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float prob = __builtin_amdgcn_exp2f(fmaf(S[r], c, -lse2));
+            ds[r] = prob * (dP[r] - dl);
+        }
+        bf16x8 dSb[2];
+        pack16(ds, dSb);
+        transposed_times_packed<ST + K_TR>(tr_addr, dSb, dQ);                   // dQ^T += K^T dS^T
+    };
+    for (int iter = 0; iter < n_iter; iter += 2) {
+        sub_block(std::integral_constant<int, 0>{});
+        if (iter + 1 < n_iter) sub_block(std::integral_constant<int, 1>{});
+    }
+    store_columns(d_q + my_row * kD, lane, dQ, c * kLn2);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// dK, dV.  grid = (N / 128, B * heads).  LDS stage: Q and dO, each for row reads and for transposed reads.
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kNW * 64, 1) void sta_bwd_dkv_kernel(const bf16_raw *__restrict__ q,
+                                                                  const bf16_raw *__restrict__ k,
+                                                                  const bf16_raw *__restrict__ v,
+                                                                  const bf16_raw *__restrict__ d_o,
+                                                                  const float *__restrict__ lse,
+                                                                  const float *__restrict__ delta,
+                                                                  bf16_raw *__restrict__ d_k,
+                                                                  bf16_raw *__restrict__ d_v, sta::FwdParams p,
+                                                                  sta::WindowTable win)
+{
+    constexpr int OPS = 4, STAGE_B = OPS * kTileB;
+    constexpr int Q_ROWS = 0, Q_TR = kTileB, G_ROWS = 2 * kTileB, G_TR = 3 * kTileB;
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
+
+    const uint32_t kblock = blockIdx.x;
+    const uint32_t heads = p.heads;
+    const uint32_t h_local = blockIdx.y % heads, b = blockIdx.y / heads;
+    const size_t bh = (size_t)b * p.H + p.head_base + h_local;
+    const uint32_t k_tile = (kblock * kCols) / p.P;
+    const StaBox box = sta_query_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1],
+                                             win.w[h_local][2], k_tile);
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, hb = lane >> 5;
+
+    const size_t head_row = bh * p.N;
+    const size_t my_row = head_row + (size_t)kblock * kCols + (size_t)wave * 32;
+    const char *qh = reinterpret_cast<const char *>(q + head_row * kD);
+    const char *gh = reinterpret_cast<const char *>(d_o + head_row * kD);
+
+    uint32_t off_rows[2], off_tr[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = 4 * (2 * wave + i) + (lane >> 4);
+        off_rows[i] = src_chunk_offset(row, lane & 15, false);
+        off_tr[i] = src_chunk_offset(row, lane & 15, true);
+    }
+    // Row statistics of the sub-block being fetched: rows 8*g + 4*hb + t of it, one float4 per g.
+    floatx4 lse_next[4], dl_next[4];
+    auto issue_loads = [&](int stage, uint32_t first_row) {
+        const size_t base = (size_t)first_row * kRowB;
+        char *dst = smem + stage * STAGE_B + (2 * wave) * 1024;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off_rows[i]),
+                                             STA_LDS_PTR(dst + Q_ROWS + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off_tr[i]),
+                                             STA_LDS_PTR(dst + Q_TR + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off_rows[i]),
+                                             STA_LDS_PTR(dst + G_ROWS + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off_tr[i]),
+                                             STA_LDS_PTR(dst + G_TR + i * 1024), 16, 0, 0);
+        }
+        const size_t stat = head_row + first_row + 4 * hb;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            lse_next[g] = *reinterpret_cast<const floatx4 *>(lse + stat + 8 * g);
+            dl_next[g] = *reinterpret_cast<const floatx4 *>(delta + stat + 8 * g);
+        }
+    };
+
+    uint32_t row_addr[8], tr_addr[4];
+    operand_addresses((uint32_t)(uintptr_t)smem, lane, row_addr, tr_addr);
+
+    bf16x8 Kr[8], Vr[8];
+    load_resident(k + my_row * kD, lane, Kr);
+    load_resident(v + my_row * kD, lane, Vr);
+    const float c = p.scale_log2e;
+
+    floatx16 dK[4], dV[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            dK[db][r] = 0.f;
+            dV[db][r] = 0.f;
+        }
+
+    BoxWalk walk;
+    walk.start(box, p.n_h, p.n_w, p.P);
+    const int n_iter = box.count() * walk.sub_per_tile;
+    int issued = 0;
+    auto issue_next = [&]() {
+        if (issued < n_iter) {
+            issue_loads(issued & 1, walk.next_row);
+            walk.advance();
+            ++issued;
+        }
+    };
+    issue_next();
+
+    auto sub_block = [&](auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value * STAGE_B;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        float lse2[16], dl[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                lse2[4 * g + t] = lse_next[g][t] * kLog2e;
+                dl[4 * g + t] = dl_next[g][t];
+            }
+        __syncthreads();
+        issue_next();
+        const floatx16 S = rows_times_resident<ST + Q_ROWS>(row_addr, Kr);     // S  = Q K^T   (queries x keys)
+        const floatx16 dP = rows_times_resident<ST + G_ROWS>(row_addr, Vr);    // dP = dO V^T
+        float prob[16], ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            prob[r] = __builtin_amdgcn_exp2f(fmaf(S[r], c, -lse2[r]));
+            ds[r] = prob[r] * (dP[r] - dl[r]);
+        }
+        bf16x8 Pb[2], dSb[2];
+        pack16(prob, Pb);
+        pack16(ds, dSb);
+        transposed_times_packed<ST + G_TR>(tr_addr, Pb, dV);                    // dV^T += dO^T P
+        transposed_times_packed<ST + Q_TR>(tr_addr, dSb, dK);                   // dK^T += Q^T dS
+    };
+    for (int iter = 0; iter < n_iter; iter += 2) {
+        sub_block(std::integral_constant<int, 0>{});
+        if (iter + 1 < n_iter) sub_block(std::integral_constant<int, 1>{});
+    }
+    store_columns(d_k + my_row * kD, lane, dK, c * kLn2);
+    store_columns(d_v + my_row * kD, lane, dV, 1.0f);
+}
+
+}  // namespace
+
+namespace sta {
+
+bool backward_supported(int P, int D) { return D == kD && P > 0 && P % kCols == 0; }
+
+hipError_t launch_backward(const void *q, const void *k, const void *v, const void *o, const void *d_o, const float *lse,
+                           float *delta, bool compute_delta, void *d_q, void *d_k, void *d_v, int B,
+                           const FwdParams &p, const WindowTable &win, hipStream_t stream)
+{
+    if (!backward_supported((int)p.P, kD)) return hipErrorInvalidValue;
+    const bf16_raw *qq = static_cast<const bf16_raw *>(q), *kk = static_cast<const bf16_raw *>(k);
+    const bf16_raw *vv = static_cast<const bf16_raw *>(v), *gg = static_cast<const bf16_raw *>(d_o);
+    if (compute_delta) {
+        const size_t rows = (size_t)B * p.H * p.N;   // all heads of the tensor at once
+        sta_bwd_delta_kernel<<<dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, stream>>>(
+            static_cast<const uint4 *>(o), static_cast<const uint4 *>(d_o), delta, rows);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid(p.N / kCols, (uint32_t)B * p.heads), block(kNW * 64);
+    sta_bwd_dq_kernel<<<grid, block, 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_q), p, win);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    sta_bwd_dkv_kernel<<<grid, block, 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_k),
+                                                   static_cast<bf16_raw *>(d_v), p, win);
+    return hipGetLastError();
+}
+
+}  // namespace sta

@@ -52,6 +52,13 @@ hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, 
 bool forward_supported(int P, int D);
 extern bool g_force_generic;   // debugging aid: route every shape through the generic kernel
 
+// ---- gradients ---------------------------------------------------------------
+// delta: float [B, H, N] scratch (dO_i . O_i per query row), filled by the call when compute_delta is set.
+hipError_t launch_backward(const void *q, const void *k, const void *v, const void *o, const void *d_o, const float *lse,
+                           float *delta, bool compute_delta, void *d_q, void *d_k, void *d_v, int B,
+                           const FwdParams &p, const WindowTable &win, hipStream_t stream);
+bool backward_supported(int P, int D);
+
 // ---- reductions around the attention kernel ----------------------------------
 constexpr int kMseSlices = 64;     // partial sums per (batch, head) slab
 hipError_t launch_head_mse(const void *a, const void *b, int B, int H, size_t elems_per_head, double *partial,

@@ -111,6 +111,14 @@ def make_qkv(w: Workload, device="cpu"):
     return tuple(out)
 
 
+def make_dout(w: Workload):
+    """Upstream gradient of the attention output for the gradient tests, [B, H, N, D] in raster order: N(0,1)
+    drawn on the host from its own generator (seed + 7919), rounded to bf16."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(w.seed + 7919)
+    return torch.randn((w.B, w.H, w.N, w.D), generator=g, dtype=torch.float32).to(torch.bfloat16)
+
+
 def make_qkv_device(w: Workload, device="cuda:0"):
     """Same distribution drawn directly on the device (benchmark-only inputs
     for sizes where a host draw would dominate the run; not used for parity)."""

@@ -1,0 +1,145 @@
+"""GPU parity tests of the gradient entry point (sta_backward) against the fp64 oracle, through the C ABI.
+The chain under test: tile_permute(Q, K, V, dO) -> sta_forward_lse -> sta_backward -> untile(dQ, dK, dV)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_04507_amd as sta
+import synth_inputs as syn
+from oracle import sta_oracle as orc
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+# Gradient tolerance.  Inputs are exact bf16; the kernel rounds P and dS to bf16 before the matrix products
+# (relative 2^-9 per element, independent, summed over hundreds to thousands of terms) and the results to bf16
+# (2^-9 per element), so a relative Frobenius error of about 2^-9 .. 2^-8 = 2e-3 .. 4e-3 is what the
+# arithmetic gives (measured: 2.3e-3 .. 2.4e-3 on every tensor); the gate is 3.3 times the measured value.  The element-wise gate is relative to the largest reference
+# entry of the tensor, because single gradients can be arbitrarily close to zero.
+GRAD_REL_FRO_TOL = 8e-3
+GRAD_COSINE_MIN = 0.9999
+GRAD_MAX_REL_TO_PEAK = 2e-2
+
+
+def assert_grad_parity(got, ref, label):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert np.isfinite(got).all(), label + ": non-finite gradient"
+    st = gu.error_stats(got, ref)
+    peak = np.abs(ref).max()
+    msg = "%s %s peak %.3g" % (label, st, peak)
+    assert st["rel_fro"] <= GRAD_REL_FRO_TOL, msg
+    assert st["cosine"] >= GRAD_COSINE_MIN, msg
+    assert st["max_abs"] <= GRAD_MAX_REL_TO_PEAK * peak, msg
+    return st
+
+
+def gpu_backward(w, q, k, v, g, scale=0.0):
+    """Returns raster-order dQ, dK, dV (bf16, host) from the HIP chain."""
+    tiled = []
+    for x in (q, k, v, g):
+        xd = x.to(DEV)
+        xt = torch.empty(xd.shape, dtype=torch.bfloat16, device=DEV)
+        sta.sta_tile_permute(xd, xt, w.grid, w.tile)
+        tiled.append(xt)
+    qt, kt, vt, gt = tiled
+    ot = torch.empty_like(qt)
+    lse = torch.empty(qt.shape[:3], dtype=torch.float32, device=DEV)
+    sta.sta_forward_lse(qt, kt, vt, ot, lse, w.grid, w.tile, w.window_tiles, scale=scale)
+    ws = torch.empty(sta.sta_backward_workspace_bytes(w.B, w.H, w.grid) // 4, dtype=torch.float32, device=DEV)
+    grads_t = [torch.full_like(qt, float("nan")) for _ in range(3)]
+    sta.sta_backward(qt, kt, vt, ot, gt, lse, grads_t[0], grads_t[1], grads_t[2], w.grid, w.tile, w.window_tiles, ws,
+                     scale=scale)
+    out = []
+    for gt_ in grads_t:
+        r = torch.full_like(gt_, float("nan"))
+        sta.sta_untile(gt_, r, w.grid, w.tile)
+        out.append(r)
+    torch.cuda.synchronize()
+    return [x.cpu() for x in out], grads_t
+
+
+def oracle_backward(w, q, k, v, g, b, h, scale=None, query_idx=None, key_idx=None):
+    f = lambda x: x[b, h].float().numpy()
+    return orc.attention_backward(f(q), f(k), f(v), f(g), w.grid, w.tile,
+                                  orc.window_tiles_to_tokens(w.window_tiles[h], w.tile), scale=scale,
+                                  query_idx=query_idx, key_idx=key_idx)
+
+
+@pytest.mark.parametrize("name,B,H,grid,tile,windows,scale", [
+    # P = 128; borders on every axis; per-head windows incl. the whole grid, an even entry and a single tile
+    ("bwd-p128", 2, 3, (4, 16, 24), (2, 8, 8), [(1, 1, 3), (3, 2, 1), (9, 9, 9)], None),
+    # P = 384 (the paper's tile), asymmetric boxes along w (5 tiles, window 3)
+    ("bwd-p384", 1, 2, (6, 8, 40), (6, 8, 8), [(1, 1, 3), (1, 1, 1)], None),
+    # one tile only, and a non-default scale
+    ("bwd-one-tile", 1, 1, (2, 8, 8), (2, 8, 8), [(1, 1, 1)], 0.05),
+    # 2D (image) case
+    ("bwd-2d", 1, 2, (1, 32, 48), (1, 8, 16), [(1, 3, 3), (1, 1, 3)], None),
+])
+def test_backward_parity_whole(name, B, H, grid, tile, windows, scale):
+    w = syn.custom(name, B, H, 128, grid, tile, windows, "bf16", seed=1201)
+    q, k, v = syn.make_qkv(w)
+    g = syn.make_dout(w)
+    (dq, dk, dv), _ = gpu_backward(w, q, k, v, g, scale=scale or 0.0)
+    for b in range(B):
+        for h in range(H):
+            rq, rk, rv = oracle_backward(w, q, k, v, g, b, h, scale=scale)
+            for label, got, ref in (("dQ", dq, rq), ("dK", dk, rk), ("dV", dv, rv)):
+                st = assert_grad_parity(got[b, h].float().numpy(), ref, "%s %s b%d h%d" % (name, label, b, h))
+                print(name, label, b, h, st)
+
+
+def test_backward_is_bit_reproducible():
+    w = syn.custom("bwd-repro", 1, 2, 128, (4, 16, 16), (2, 8, 8), [(3, 3, 1), (1, 1, 3)], "bf16", seed=1202)
+    q, k, v = syn.make_qkv(w)
+    g = syn.make_dout(w)
+    first, _ = gpu_backward(w, q, k, v, g)
+    for _ in range(3):
+        again, _ = gpu_backward(w, q, k, v, g)
+        for a, bb in zip(first, again):
+            assert torch.equal(a.view(torch.int16), bb.view(torch.int16))
+
+
+def test_backward_full_size_sampled():
+    """Headline shape (115,200 tokens, window 3x3x3), one head checked: dQ on sampled query rows, dK/dV on sampled
+    key rows of a corner tile and an interior tile (each summed by the oracle over every query that keeps them)."""
+    w = syn.workload("C4")
+    q, k, v = syn.make_qkv(w)
+    g = syn.make_dout(w)
+    (dq, dk, dv), _ = gpu_backward(w, q, k, v, g)
+    order = orc.tile_order(w.grid, w.tile)
+    nt, nh, nw = w.tile_grid
+    tiles = [0, ((nt // 2) * nh + nh // 2) * nw + nw // 2]
+    rng = np.random.default_rng(77)
+    for h in (5,):
+        qidx = gu.stratified_query_sample(w, 40, [], seed=400 + h)
+        kidx = np.unique(np.concatenate([order[t * w.P + rng.integers(0, w.P, size=3)] for t in tiles])).astype(np.int64)
+        rq, rk, rv = oracle_backward(w, q, k, v, g, 0, h, query_idx=qidx, key_idx=kidx)
+        assert_grad_parity(dq[0, h][qidx].float().numpy(), rq, "C4 dQ h%d" % h)
+        assert_grad_parity(dk[0, h][kidx].float().numpy(), rk, "C4 dK h%d" % h)
+        assert_grad_parity(dv[0, h][kidx].float().numpy(), rv, "C4 dV h%d" % h)
+
+
+def test_backward_errors():
+    w = syn.custom("bwd-err", 1, 1, 128, (2, 8, 8), (2, 8, 8), [(1, 1, 1)], "bf16", seed=1203)
+    t = lambda: torch.zeros((1, 1, w.N, 128), dtype=torch.bfloat16, device=DEV)
+    qt, kt, vt, ot, gt, dq, dk, dv = (t() for _ in range(8))
+    lse = torch.zeros((1, 1, w.N), dtype=torch.float32, device=DEV)
+    ws = torch.zeros(w.N, dtype=torch.float32, device=DEV)
+    with pytest.raises(sta.StaError) as e:       # workspace too small
+        sta.sta_backward(qt, kt, vt, ot, gt, lse, dq, dk, dv, w.grid, w.tile, w.window_tiles, ws[: w.N // 2])
+    assert e.value.status == 6
+    with pytest.raises(sta.StaError) as e:       # output aliases an input
+        sta.sta_backward(qt, kt, vt, ot, gt, lse, qt, dk, dv, w.grid, w.tile, w.window_tiles, ws)
+    assert e.value.status == 5
+    with pytest.raises(sta.StaError) as e:       # two outputs alias
+        sta.sta_backward(qt, kt, vt, ot, gt, lse, dq, dq, dv, w.grid, w.tile, w.window_tiles, ws)
+    assert e.value.status == 5
+    # head dimension 64 and a 64-token tile have no gradient kernel
+    t64 = lambda: torch.zeros((1, 1, 64, 64), dtype=torch.bfloat16, device=DEV)
+    a = [t64() for _ in range(8)]
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_backward(*a[:5], torch.zeros((1, 1, 64), dtype=torch.float32, device=DEV), *a[5:], (1, 8, 8), (1, 8, 8),
+                         [(1, 1, 1)], ws)
+    assert e.value.status == 4
