@@ -13,7 +13,8 @@
 //   sta_bwd_dq_kernel     one workgroup per query block, walks the key tiles of its window (as the forward
 //                         kernel does): 3 MFMA products per block (K Q^T, V dO^T, K^T dS^T);
 //   sta_bwd_dkv_kernel    one workgroup per key block, walks the QUERY tiles that keep its key tile (the
-//                         transposed box): 4 MFMA products per block (Q K^T, dO V^T, dO^T P, Q^T dS).
+//                         transposed box): 4 MFMA products per block (Q K^T, dO V^T, dO^T P, Q^T dS), split
+//                         over pairs of waves.
 // S and dP are thus computed twice (7 products against the 5 of a single-pass scheme with atomics on dQ).
 //
 // Same MFMA formulation as the forward kernel: the block is held transposed so that one lane owns one column
@@ -301,21 +302,32 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// dK, dV.  grid = (N / 128, B * heads).  LDS stage: Q and dO, each for row reads and for transposed reads.
+// dK, dV.  grid = (N / 128, B * heads), 8 waves.  LDS stage: Q and dO, each for row reads and for transposed
+// reads.  The four 32-key column blocks of the workgroup are each served by a PAIR of waves (w and w + 4, which
+// share a SIMD): wave w holds K and accumulates dV (S = Q K^T, P, dV^T += dO^T P), wave w + 4 holds V and
+// accumulates dK (dP = dO V^T, dS = P o (dP - delta), dK^T += Q^T dS).  P, rounded to bf16 and packed as the
+// MFMA B operand, goes from the first to the second through 2 KB of LDS.  Four matrix products per block, no
+// duplicate work inside the kernel, and each wave keeps one accumulator set: 2 waves per SIMD fit.
 // ---------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kNW * 64, 1) void sta_bwd_dkv_kernel(const bf16_raw *__restrict__ q,
-                                                                  const bf16_raw *__restrict__ k,
-                                                                  const bf16_raw *__restrict__ v,
-                                                                  const bf16_raw *__restrict__ d_o,
-                                                                  const float *__restrict__ lse,
-                                                                  const float *__restrict__ delta,
-                                                                  bf16_raw *__restrict__ d_k,
-                                                                  bf16_raw *__restrict__ d_v, sta::FwdParams p,
-                                                                  sta::WindowTable win)
+__device__ __forceinline__ void lds_write_b128(uint32_t addr, bf16x8 v)
+{
+    asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+
+__global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__restrict__ q,
+                                                             const bf16_raw *__restrict__ k,
+                                                             const bf16_raw *__restrict__ v,
+                                                             const bf16_raw *__restrict__ d_o,
+                                                             const float *__restrict__ lse,
+                                                             const float *__restrict__ delta,
+                                                             bf16_raw *__restrict__ d_k,
+                                                             bf16_raw *__restrict__ d_v, sta::FwdParams p,
+                                                             sta::WindowTable win)
 {
     constexpr int OPS = 4, STAGE_B = OPS * kTileB;
     constexpr int Q_ROWS = 0, Q_TR = kTileB, G_ROWS = 2 * kTileB, G_TR = 3 * kTileB;
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
+    constexpr int P_XCHG = 2 * STAGE_B;                 // 4 column blocks x 64 lanes x 32 B
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 4 * 2048];
 
     const uint32_t kblock = blockIdx.x;
     const uint32_t heads = p.heads;
@@ -327,59 +339,52 @@ __global__ __launch_bounds__(kNW * 64, 1) void sta_bwd_dkv_kernel(const bf16_raw
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63, hb = lane >> 5;
+    const bool probs_role = wave < 4;                   // S, P, dV; the other role: dP, dS, dK
+    const int col_block = wave & 3;
 
     const size_t head_row = bh * p.N;
-    const size_t my_row = head_row + (size_t)kblock * kCols + (size_t)wave * 32;
+    const size_t my_row = head_row + (size_t)kblock * kCols + (size_t)col_block * 32;
     const char *qh = reinterpret_cast<const char *>(q + head_row * kD);
     const char *gh = reinterpret_cast<const char *>(d_o + head_row * kD);
 
-    uint32_t off_rows[2], off_tr[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = 4 * (2 * wave + i) + (lane >> 4);
-        off_rows[i] = src_chunk_offset(row, lane & 15, false);
-        off_tr[i] = src_chunk_offset(row, lane & 15, true);
-    }
-    // Row statistics of the sub-block being fetched: rows 8*g + 4*hb + t of it, one float4 per g.
-    floatx4 lse_next[4], dl_next[4];
+    // DMA: each operand is 8 instructions of 1 KB (4 rows); wave w issues instruction w of each.
+    const int dma_row = 4 * wave + (lane >> 4);
+    const uint32_t off_rows = src_chunk_offset(dma_row, lane & 15, false);
+    const uint32_t off_tr = src_chunk_offset(dma_row, lane & 15, true);
+    // Row statistics of the sub-block being fetched (lse for the first role, delta for the second): rows
+    // 8*g + 4*hb + t of it, one float4 per g.
+    const float *stat = probs_role ? lse : delta;
+    floatx4 stat_next[4];
     auto issue_loads = [&](int stage, uint32_t first_row) {
         const size_t base = (size_t)first_row * kRowB;
-        char *dst = smem + stage * STAGE_B + (2 * wave) * 1024;
+        char *dst = smem + stage * STAGE_B + wave * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off_rows),
+                                         STA_LDS_PTR(dst + Q_ROWS), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off_tr),
+                                         STA_LDS_PTR(dst + Q_TR), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off_rows),
+                                         STA_LDS_PTR(dst + G_ROWS), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off_tr),
+                                         STA_LDS_PTR(dst + G_TR), 16, 0, 0);
+        const size_t at = head_row + first_row + 4 * hb;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off_rows[i]),
-                                             STA_LDS_PTR(dst + Q_ROWS + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off_tr[i]),
-                                             STA_LDS_PTR(dst + Q_TR + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off_rows[i]),
-                                             STA_LDS_PTR(dst + G_ROWS + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off_tr[i]),
-                                             STA_LDS_PTR(dst + G_TR + i * 1024), 16, 0, 0);
-        }
-        const size_t stat = head_row + first_row + 4 * hb;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            lse_next[g] = *reinterpret_cast<const floatx4 *>(lse + stat + 8 * g);
-            dl_next[g] = *reinterpret_cast<const floatx4 *>(delta + stat + 8 * g);
-        }
+        for (int g = 0; g < 4; ++g) stat_next[g] = *reinterpret_cast<const floatx4 *>(stat + at + 8 * g);
     };
 
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
     uint32_t row_addr[8], tr_addr[4];
-    operand_addresses((uint32_t)(uintptr_t)smem, lane, row_addr, tr_addr);
+    operand_addresses(smem_addr, lane, row_addr, tr_addr);
+    const uint32_t xchg_addr = smem_addr + P_XCHG + col_block * 2048 + lane * 32;
 
-    bf16x8 Kr[8], Vr[8];
-    load_resident(k + my_row * kD, lane, Kr);
-    load_resident(v + my_row * kD, lane, Vr);
+    bf16x8 resident[8];                                  // K rows (first role) or V rows (second role)
+    load_resident((probs_role ? k : v) + my_row * kD, lane, resident);
     const float c = p.scale_log2e;
 
-    floatx16 dK[4], dV[4];
+    floatx16 acc[4];                                     // dV^T (first role) or dK^T (second role)
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            dK[db][r] = 0.f;
-            dV[db][r] = 0.f;
-        }
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
     BoxWalk walk;
     walk.start(box, p.n_h, p.n_w, p.P);
@@ -397,36 +402,50 @@ __global__ __launch_bounds__(kNW * 64, 1) void sta_bwd_dkv_kernel(const bf16_raw
     auto sub_block = [&](auto stage_c) {
         constexpr int ST = decltype(stage_c)::value * STAGE_B;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        float lse2[16], dl[16];
+        float st[16];
 #pragma unroll
         for (int g = 0; g < 4; ++g)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                lse2[4 * g + t] = lse_next[g][t] * kLog2e;
-                dl[4 * g + t] = dl_next[g][t];
-            }
-        __syncthreads();
+            for (int t = 0; t < 4; ++t) st[4 * g + t] = stat_next[g][t];
+        __syncthreads();       // the stage is complete; the other stage and the exchange buffer are free
         issue_next();
-        const floatx16 S = rows_times_resident<ST + Q_ROWS>(row_addr, Kr);     // S  = Q K^T   (queries x keys)
-        const floatx16 dP = rows_times_resident<ST + G_ROWS>(row_addr, Vr);    // dP = dO V^T
-        float prob[16], ds[16];
+        floatx16 X;
+        if (probs_role) {
+            X = rows_times_resident<ST + Q_ROWS>(row_addr, resident);           // S = Q K^T (queries x keys)
+            float prob[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            prob[r] = __builtin_amdgcn_exp2f(fmaf(S[r], c, -lse2[r]));
-            ds[r] = prob[r] * (dP[r] - dl[r]);
+            for (int r = 0; r < 16; ++r) prob[r] = __builtin_amdgcn_exp2f(fmaf(X[r], c, -st[r] * kLog2e));
+            bf16x8 Pb[2];
+            pack16(prob, Pb);
+            lds_write_b128(xchg_addr, Pb[0]);
+            lds_write_b128(xchg_addr + 16, Pb[1]);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            transposed_times_packed<ST + G_TR>(tr_addr, Pb, acc);               // dV^T += dO^T P
+        } else {
+            X = rows_times_resident<ST + G_ROWS>(row_addr, resident);           // dP = dO V^T
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            bf16x8 Pb[2];
+            Pb[0] = ds_read_b128_at<0>(xchg_addr);
+            Pb[1] = ds_read_b128_at<16>(xchg_addr);
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(Pb[0]), "+v"(Pb[1]));
+            float ds[16];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ds[8 * j + e] = static_cast<float>(Pb[j][e]) * (X[8 * j + e] - st[8 * j + e]);
+            bf16x8 dSb[2];
+            pack16(ds, dSb);
+            transposed_times_packed<ST + Q_TR>(tr_addr, dSb, acc);              // dK^T += Q^T dS
         }
-        bf16x8 Pb[2], dSb[2];
-        pack16(prob, Pb);
-        pack16(ds, dSb);
-        transposed_times_packed<ST + G_TR>(tr_addr, Pb, dV);                    // dV^T += dO^T P
-        transposed_times_packed<ST + Q_TR>(tr_addr, dSb, dK);                   // dK^T += Q^T dS
     };
     for (int iter = 0; iter < n_iter; iter += 2) {
         sub_block(std::integral_constant<int, 0>{});
         if (iter + 1 < n_iter) sub_block(std::integral_constant<int, 1>{});
     }
-    store_columns(d_k + my_row * kD, lane, dK, c * kLn2);
-    store_columns(d_v + my_row * kD, lane, dV, 1.0f);
+    if (probs_role) store_columns(d_v + my_row * kD, lane, acc, 1.0f);
+    else store_columns(d_k + my_row * kD, lane, acc, c * kLn2);
 }
 
 }  // namespace
@@ -453,7 +472,7 @@ hipError_t launch_backward(const void *q, const void *k, const void *v, const vo
     sta_bwd_dq_kernel<<<grid, block, 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_q), p, win);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    sta_bwd_dkv_kernel<<<grid, block, 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_k),
+    sta_bwd_dkv_kernel<<<grid, dim3(512), 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_k),
                                                    static_cast<bf16_raw *>(d_v), p, win);
     return hipGetLastError();
 }
