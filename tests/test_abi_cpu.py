@@ -153,3 +153,26 @@ def test_block_census_errors():
     with pytest.raises(sta.StaError) as e:
         sta.sta_block_census(7, (4, 4, 4), (2, 2, 2), (3, 3, 3))
     assert e.value.status == 4
+
+
+def test_query_tile_box_is_the_transpose_of_the_key_tile_box():
+    """For every key tile, the query tiles whose box contains it, by scanning all boxes, equal the closed form."""
+    for n, w in itertools.product(range(1, 9), range(1, 19)):
+        grid = (1, 1, n)
+        for k in range(n):
+            scan = [q for q in range(n)
+                    if sta.sta_key_tile_box(grid, (1, 1, w), (0, 0, q))[0][2] <= k
+                    <= sta.sta_key_tile_box(grid, (1, 1, w), (0, 0, q))[1][2]]
+            lo, hi = sta.sta_query_tile_box(grid, (1, 1, w), (0, 0, k))
+            assert scan == list(range(lo[2], hi[2] + 1)), (n, w, k)
+    # three axes at once, against the oracle's key-tile lists
+    grid, tile, win = (4, 6, 10), (1, 2, 2), (3, 1, 5)
+    n = (4, 3, 5)
+    counts, lists = orc.key_tiles(grid, tile, orc.window_tiles_to_tokens(win, tile))
+    for kt in range(60):
+        keepers = sorted(q for q in range(60) if kt in lists[q, :counts[q]])
+        c = np.unravel_index(kt, n)
+        lo, hi = sta.sta_query_tile_box(n, win, tuple(int(x) for x in c))
+        box = sorted(int(np.ravel_multi_index((a, b, d), n)) for a in range(lo[0], hi[0] + 1)
+                     for b in range(lo[1], hi[1] + 1) for d in range(lo[2], hi[2] + 1))
+        assert keepers == box, kt
