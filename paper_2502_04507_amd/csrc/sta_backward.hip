@@ -75,30 +75,33 @@ __device__ __forceinline__ floatx16 rows_times_resident(const uint32_t (&row_add
 }
 
 // acc[db](32 channels x 32 columns) += A B with A = the staged sub-block at OFF read transposed (A rows =
-// channels, k = its 32 tokens in accumulator order) and B = the two packed halves of an accumulator.
+// channels, k = its 32 tokens in accumulator order) and B = the two packed halves of an accumulator.  The
+// reads of the first 16 tokens can be issued early (prefetch), before B exists, so that their latency hides
+// behind the arithmetic that produces B.
 template <int OFF>
-__device__ __forceinline__ void transposed_times_packed(const uint32_t (&tr_addr)[4], const bf16x8 (&packed)[2],
-                                                        floatx16 (&acc)[4])
-{
-    typedef short shortx8 __attribute__((ext_vector_type(8)));
+struct TransposedProduct {
     shortx4 frag[2][4][2];
-    pv_issue<OFF, 4, kRowB>(frag[0], tr_addr);
-    pv_issue<OFF + 16 * kRowB, 4, kRowB>(frag[1], tr_addr);
-    pv_wait<8>(frag[0]);
+    __device__ __forceinline__ void prefetch(const uint32_t (&tr_addr)[4]) { pv_issue<OFF, 4, kRowB>(frag[0], tr_addr); }
+    __device__ __forceinline__ void run(const uint32_t (&tr_addr)[4], const bf16x8 (&packed)[2], floatx16 (&acc)[4])
+    {
+        typedef short shortx8 __attribute__((ext_vector_type(8)));
+        pv_issue<OFF + 16 * kRowB, 4, kRowB>(frag[1], tr_addr);
+        pv_wait<8>(frag[0]);
 #pragma unroll
-    for (int db = 0; db < 4; ++db) {
-        const shortx8 a = __builtin_shufflevector(frag[0][db][0], frag[0][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
-        acc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, a), packed[0], acc[db]);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    pv_wait<0>(frag[1]);
+        for (int db = 0; db < 4; ++db) {
+            const shortx8 a = __builtin_shufflevector(frag[0][db][0], frag[0][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
+            acc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, a), packed[0], acc[db]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        pv_wait<0>(frag[1]);
 #pragma unroll
-    for (int db = 0; db < 4; ++db) {
-        const shortx8 a = __builtin_shufflevector(frag[1][db][0], frag[1][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
-        acc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, a), packed[1], acc[db]);
+        for (int db = 0; db < 4; ++db) {
+            const shortx8 a = __builtin_shufflevector(frag[1][db][0], frag[1][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
+            acc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, a), packed[1], acc[db]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-}
+};
 
 __device__ __forceinline__ void pack16(const float (&x)[16], bf16x8 (&out)[2])
 {
@@ -284,6 +287,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
         issue_next();
         const floatx16 S = rows_times_resident<ST + K_ROWS>(row_addr, Qr);     // S^T  = K Q^T   (keys x queries)
         const floatx16 dP = rows_times_resident<ST + V_ROWS>(row_addr, Gr);    // dP^T = V dO^T
+        TransposedProduct<ST + K_TR> k_t;
+        k_t.prefetch(tr_addr);
         float ds[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -292,7 +297,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
         }
         bf16x8 dSb[2];
         pack16(ds, dSb);
-        transposed_times_packed<ST + K_TR>(tr_addr, dSb, dQ);                   // dQ^T += K^T dS^T
+        k_t.run(tr_addr, dSb, dQ);                                              // dQ^T += K^T dS^T
     };
     for (int iter = 0; iter < n_iter; iter += 2) {
         sub_block(std::integral_constant<int, 0>{});
@@ -326,7 +331,7 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
 {
     constexpr int OPS = 4, STAGE_B = OPS * kTileB;
     constexpr int Q_ROWS = 0, Q_TR = kTileB, G_ROWS = 2 * kTileB, G_TR = 3 * kTileB;
-    constexpr int P_XCHG = 2 * STAGE_B;                 // 4 column blocks x 64 lanes x 32 B
+    constexpr int P_XCHG = 2 * STAGE_B;                 // 4 column blocks x 2 planes x 64 lanes x 16 B
     __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 4 * 2048];
 
     const uint32_t kblock = blockIdx.x;
@@ -374,7 +379,7 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
     const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
     uint32_t row_addr[8], tr_addr[4];
     operand_addresses(smem_addr, lane, row_addr, tr_addr);
-    const uint32_t xchg_addr = smem_addr + P_XCHG + col_block * 2048 + lane * 32;
+    const uint32_t xchg_addr = smem_addr + P_XCHG + col_block * 2048 + lane * 16;   // two planes of 1 KB, contiguous per wave
 
     bf16x8 resident[8];                                  // K rows (first role) or V rows (second role)
     load_resident((probs_role ? k : v) + my_row * kD, lane, resident);
@@ -412,23 +417,26 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
         floatx16 X;
         if (probs_role) {
             X = rows_times_resident<ST + Q_ROWS>(row_addr, resident);           // S = Q K^T (queries x keys)
+            TransposedProduct<ST + G_TR> g_t;
+            g_t.prefetch(tr_addr);
             float prob[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) prob[r] = __builtin_amdgcn_exp2f(fmaf(X[r], c, -st[r] * kLog2e));
             bf16x8 Pb[2];
             pack16(prob, Pb);
             lds_write_b128(xchg_addr, Pb[0]);
-            lds_write_b128(xchg_addr + 16, Pb[1]);
+            lds_write_b128(xchg_addr + 1024, Pb[1]);
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             __builtin_amdgcn_s_barrier();
-            transposed_times_packed<ST + G_TR>(tr_addr, Pb, acc);               // dV^T += dO^T P
+            g_t.run(tr_addr, Pb, acc);                                          // dV^T += dO^T P
         } else {
             X = rows_times_resident<ST + G_ROWS>(row_addr, resident);           // dP = dO V^T
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            TransposedProduct<ST + Q_TR> q_t;
+            q_t.prefetch(tr_addr);
             __builtin_amdgcn_s_barrier();
             bf16x8 Pb[2];
             Pb[0] = ds_read_b128_at<0>(xchg_addr);
-            Pb[1] = ds_read_b128_at<16>(xchg_addr);
+            Pb[1] = ds_read_b128_at<1024>(xchg_addr);
             asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(Pb[0]), "+v"(Pb[1]));
             float ds[16];
 #pragma unroll
@@ -437,7 +445,7 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
                 for (int e = 0; e < 8; ++e) ds[8 * j + e] = static_cast<float>(Pb[j][e]) * (X[8 * j + e] - st[8 * j + e]);
             bf16x8 dSb[2];
             pack16(ds, dSb);
-            transposed_times_packed<ST + Q_TR>(tr_addr, dSb, acc);              // dK^T += Q^T dS
+            q_t.run(tr_addr, dSb, acc);                                         // dK^T += Q^T dS
         }
     };
     for (int iter = 0; iter < n_iter; iter += 2) {
