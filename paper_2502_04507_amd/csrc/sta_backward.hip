@@ -21,8 +21,12 @@
 // (a query in the dQ kernel, a key in the dK/dV kernel), and the bf16-rounded P or dS goes from the
 // accumulators straight into the B operand of the next product, the contraction index being fed in
 // accumulator order.  Staged operands sit row-major in LDS (256 B per token), brought in by
-// global_load_lds; an operand that is read both by rows (A rows = tokens) and transposed (A rows = channels)
-// is staged twice, once with each of the two XOR swizzles that make the respective reads bank-conflict free.
+// global_load_lds.  An operand may be read both by rows (A rows = tokens, 16-byte reads) and transposed
+// (A rows = channels, ds_read_b64_tr_b16); one XOR swizzle of the 16-byte chunks keeps both conflict-free:
+// chunk c of row r sits at position c ^ swz(r), swz(r) = ((r & 3) << 2) | ((r >> 2) & 3).  Over 16 consecutive
+// rows swz takes 16 different values (row reads of one chunk column hit 16 different bank groups), and over the
+// 4 rows a transposing read touches its upper two bits differ (the four 64-byte channel groups go to four
+// different quarters of the row).
 // Head dimension 128; tokens per tile a multiple of 128.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -42,13 +46,25 @@ constexpr int kCols = kNW * 32;        // queries (dQ kernel) or keys (dK/dV ker
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
 // Byte offset, inside a row-major [32][128] bf16 sub-block in global memory, of the 16-byte chunk that belongs
-// at LDS slot `slot` (0..15) of row `row` under the row-read swizzle (c ^ (row & 15)) or the transposed-read
-// swizzle (c ^ ((row & 3) << 2)).
-__device__ __forceinline__ uint32_t src_chunk_offset(int row, int slot, bool transposed_read)
+// at LDS slot `slot` (0..15) of row `row`.
+__device__ __forceinline__ uint32_t src_chunk_offset(int row, int slot)
 {
-    const int chunk = transposed_read ? (slot ^ ((row & 3) << 2)) : (slot ^ (row & 15));
-    return (uint32_t)(row * kRowB + (chunk << 4));
+    return (uint32_t)(row * kRowB + ((slot ^ swz(row)) << 4));
+}
+
+// Issue the 8 transposing reads of one 16-token group.  The second read of each pair is 8 rows further down,
+// where swz differs in bit 1, so it has its own address.
+template <int BASE>
+__device__ __forceinline__ void tr_issue(shortx4 (&frag)[4][2], const uint32_t (&tr_addr)[2][4])
+{
+    static_for<0, 4>([&](auto dbi) {
+        constexpr int db = decltype(dbi)::value;
+        frag[db][0] = ds_read_tr16<BASE>(tr_addr[0][db]);
+        frag[db][1] = ds_read_tr16<BASE + 8 * kRowB>(tr_addr[1][db]);
+    });
 }
 
 // acc(32 x 32) = A B with A = a staged sub-block read by rows (A rows = its 32 tokens, k = channels) at byte
@@ -81,11 +97,11 @@ __device__ __forceinline__ floatx16 rows_times_resident(const uint32_t (&row_add
 template <int OFF>
 struct TransposedProduct {
     shortx4 frag[2][4][2];
-    __device__ __forceinline__ void prefetch(const uint32_t (&tr_addr)[4]) { pv_issue<OFF, 4, kRowB>(frag[0], tr_addr); }
-    __device__ __forceinline__ void run(const uint32_t (&tr_addr)[4], const bf16x8 (&packed)[2], floatx16 (&acc)[4])
+    __device__ __forceinline__ void prefetch(const uint32_t (&tr_addr)[2][4]) { tr_issue<OFF>(frag[0], tr_addr); }
+    __device__ __forceinline__ void run(const uint32_t (&tr_addr)[2][4], const bf16x8 (&packed)[2], floatx16 (&acc)[4])
     {
         typedef short shortx8 __attribute__((ext_vector_type(8)));
-        pv_issue<OFF + 16 * kRowB, 4, kRowB>(frag[1], tr_addr);
+        tr_issue<OFF + 16 * kRowB>(frag[1], tr_addr);
         pv_wait<8>(frag[0]);
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
@@ -140,16 +156,24 @@ struct BoxWalk {
 };
 
 // Per-lane constants of the operand reads (relative to the start of a staged sub-block).
+//  Row reads: row lo, logical chunk 2*ks + hb.
+//  Transposing reads: within each block of 16 lanes, lane 4*j4 + s4 supplies 4 channels of token row
+//  4*hb + j4 (+8 for the second read of a pair); logical chunk 4*db + 2*blk + (s4 >> 1), 8-byte half s4 & 1.
 __device__ __forceinline__ void operand_addresses(uint32_t smem_addr, int lane, uint32_t (&row_addr)[8],
-                                                  uint32_t (&tr_addr)[4])
+                                                  uint32_t (&tr_addr)[2][4])
 {
     const int lo = lane & 31, hb = lane >> 5;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) row_addr[ks] = smem_addr + (uint32_t)(lo * kRowB + (((2 * ks + hb) ^ (lo & 15)) << 4));
+    for (int ks = 0; ks < 8; ++ks) row_addr[ks] = smem_addr + (uint32_t)(lo * kRowB + (((2 * ks + hb) ^ swz(lo)) << 4));
     const int j4 = (lane & 15) >> 2, s4 = lane & 3, blk = (lane >> 4) & 1;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
-        tr_addr[db] = smem_addr + (uint32_t)((4 * hb + j4) * kRowB + ((((db ^ j4) << 2) | (2 * blk + (s4 >> 1))) << 4) + 8 * (s4 & 1));
+    for (int a = 0; a < 2; ++a) {
+        const int row = 4 * hb + j4 + 8 * a;             // the +8 itself travels in the instruction's immediate
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+            tr_addr[a][db] = smem_addr + (uint32_t)((4 * hb + j4) * kRowB +
+                                                    (((4 * db + 2 * blk + (s4 >> 1)) ^ swz(row)) << 4) + 8 * (s4 & 1));
+    }
 }
 
 // Resident B-operand fragments of this wave's 32 columns (rows of x): column lo, channels 16*ks + 8*hb ..
@@ -199,7 +223,7 @@ __global__ __launch_bounds__(256) void sta_bwd_delta_kernel(const uint4 *__restr
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// dQ.  grid = (N / 128, B * heads).  LDS stage: K for row reads, K for transposed reads, V for row reads.
+// dQ.  grid = (N / 128, B * heads).  LDS stage: K (read by rows and transposed) and V (read by rows).
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw *__restrict__ q,
                                                                  const bf16_raw *__restrict__ k,
@@ -210,8 +234,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
                                                                  bf16_raw *__restrict__ d_q, sta::FwdParams p,
                                                                  sta::WindowTable win)
 {
-    constexpr int OPS = 3, STAGE_B = OPS * kTileB;
-    constexpr int K_ROWS = 0, K_TR = kTileB, V_ROWS = 2 * kTileB;
+    constexpr int OPS = 2, STAGE_B = OPS * kTileB;
+    constexpr int K_TILE = 0, V_TILE = kTileB;
     __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
 
     const uint32_t qblock = blockIdx.x;
@@ -230,28 +254,22 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
     const char *vh = reinterpret_cast<const char *>(v + bh * p.N * kD);
 
     // DMA: each operand is 8 instructions of 1 KB (4 rows); wave w issues instructions 2w and 2w+1 of each.
-    uint32_t off_rows[2], off_tr[2];
+    uint32_t src_off[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = 4 * (2 * wave + i) + (lane >> 4);
-        off_rows[i] = src_chunk_offset(row, lane & 15, false);
-        off_tr[i] = src_chunk_offset(row, lane & 15, true);
-    }
+    for (int i = 0; i < 2; ++i) src_off[i] = src_chunk_offset(4 * (2 * wave + i) + (lane >> 4), lane & 15);
     auto issue_loads = [&](int stage, uint32_t first_row) {
         const size_t base = (size_t)first_row * kRowB;
         char *dst = smem + stage * STAGE_B + (2 * wave) * 1024;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + base + off_rows[i]),
-                                             STA_LDS_PTR(dst + K_ROWS + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + base + off_tr[i]),
-                                             STA_LDS_PTR(dst + K_TR + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + base + off_rows[i]),
-                                             STA_LDS_PTR(dst + V_ROWS + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + base + src_off[i]),
+                                             STA_LDS_PTR(dst + K_TILE + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + base + src_off[i]),
+                                             STA_LDS_PTR(dst + V_TILE + i * 1024), 16, 0, 0);
         }
     };
 
-    uint32_t row_addr[8], tr_addr[4];
+    uint32_t row_addr[8], tr_addr[2][4];
     operand_addresses((uint32_t)(uintptr_t)smem, lane, row_addr, tr_addr);
 
     bf16x8 Qr[8], Gr[8];
@@ -285,9 +303,9 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         issue_next();
-        const floatx16 S = rows_times_resident<ST + K_ROWS>(row_addr, Qr);     // S^T  = K Q^T   (keys x queries)
-        const floatx16 dP = rows_times_resident<ST + V_ROWS>(row_addr, Gr);    // dP^T = V dO^T
-        TransposedProduct<ST + K_TR> k_t;
+        const floatx16 S = rows_times_resident<ST + K_TILE>(row_addr, Qr);     // S^T  = K Q^T   (keys x queries)
+        const floatx16 dP = rows_times_resident<ST + V_TILE>(row_addr, Gr);    // dP^T = V dO^T
+        TransposedProduct<ST + K_TILE> k_t;
         k_t.prefetch(tr_addr);
         float ds[16];
 #pragma unroll
@@ -307,8 +325,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// dK, dV.  grid = (N / 128, B * heads), 8 waves.  LDS stage: Q and dO, each for row reads and for transposed
-// reads.  The four 32-key column blocks of the workgroup are each served by a PAIR of waves (w and w + 4, which
+// dK, dV.  grid = (N / 128, B * heads), 8 waves.  LDS stage: Q and dO (each read by rows and transposed).
+// The four 32-key column blocks of the workgroup are each served by a PAIR of waves (w and w + 4, which
 // share a SIMD): wave w holds K and accumulates dV (S = Q K^T, P, dV^T += dO^T P), wave w + 4 holds V and
 // accumulates dK (dP = dO V^T, dS = P o (dP - delta), dK^T += Q^T dS).  P, rounded to bf16 and packed as the
 // MFMA B operand, goes from the first to the second through 2 KB of LDS.  Four matrix products per block, no
@@ -329,8 +347,8 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
                                                              bf16_raw *__restrict__ d_v, sta::FwdParams p,
                                                              sta::WindowTable win)
 {
-    constexpr int OPS = 4, STAGE_B = OPS * kTileB;
-    constexpr int Q_ROWS = 0, Q_TR = kTileB, G_ROWS = 2 * kTileB, G_TR = 3 * kTileB;
+    constexpr int OPS = 2, STAGE_B = OPS * kTileB;
+    constexpr int Q_TILE = 0, G_TILE = kTileB;
     constexpr int P_XCHG = 2 * STAGE_B;                 // 4 column blocks x 2 planes x 64 lanes x 16 B
     __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 4 * 2048];
 
@@ -354,8 +372,7 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
 
     // DMA: each operand is 8 instructions of 1 KB (4 rows); wave w issues instruction w of each.
     const int dma_row = 4 * wave + (lane >> 4);
-    const uint32_t off_rows = src_chunk_offset(dma_row, lane & 15, false);
-    const uint32_t off_tr = src_chunk_offset(dma_row, lane & 15, true);
+    const uint32_t src_off = src_chunk_offset(dma_row, lane & 15);
     // Row statistics of the sub-block being fetched (lse for the first role, delta for the second): rows
     // 8*g + 4*hb + t of it, one float4 per g.
     const float *stat = probs_role ? lse : delta;
@@ -363,21 +380,17 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
     auto issue_loads = [&](int stage, uint32_t first_row) {
         const size_t base = (size_t)first_row * kRowB;
         char *dst = smem + stage * STAGE_B + wave * 1024;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off_rows),
-                                         STA_LDS_PTR(dst + Q_ROWS), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off_tr),
-                                         STA_LDS_PTR(dst + Q_TR), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off_rows),
-                                         STA_LDS_PTR(dst + G_ROWS), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off_tr),
-                                         STA_LDS_PTR(dst + G_TR), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + src_off),
+                                         STA_LDS_PTR(dst + Q_TILE), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + src_off),
+                                         STA_LDS_PTR(dst + G_TILE), 16, 0, 0);
         const size_t at = head_row + first_row + 4 * hb;
 #pragma unroll
         for (int g = 0; g < 4; ++g) stat_next[g] = *reinterpret_cast<const floatx4 *>(stat + at + 8 * g);
     };
 
     const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
-    uint32_t row_addr[8], tr_addr[4];
+    uint32_t row_addr[8], tr_addr[2][4];
     operand_addresses(smem_addr, lane, row_addr, tr_addr);
     const uint32_t xchg_addr = smem_addr + P_XCHG + col_block * 2048 + lane * 16;   // two planes of 1 KB, contiguous per wave
 
@@ -416,8 +429,8 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
         issue_next();
         floatx16 X;
         if (probs_role) {
-            X = rows_times_resident<ST + Q_ROWS>(row_addr, resident);           // S = Q K^T (queries x keys)
-            TransposedProduct<ST + G_TR> g_t;
+            X = rows_times_resident<ST + Q_TILE>(row_addr, resident);           // S = Q K^T (queries x keys)
+            TransposedProduct<ST + G_TILE> g_t;
             g_t.prefetch(tr_addr);
             float prob[16];
 #pragma unroll
@@ -430,8 +443,8 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
             __builtin_amdgcn_s_barrier();
             g_t.run(tr_addr, Pb, acc);                                          // dV^T += dO^T P
         } else {
-            X = rows_times_resident<ST + G_ROWS>(row_addr, resident);           // dP = dO V^T
-            TransposedProduct<ST + Q_TR> q_t;
+            X = rows_times_resident<ST + G_TILE>(row_addr, resident);           // dP = dO V^T
+            TransposedProduct<ST + Q_TILE> q_t;
             q_t.prefetch(tr_addr);
             __builtin_amdgcn_s_barrier();
             bf16x8 Pb[2];
