@@ -225,6 +225,7 @@ __global__ __launch_bounds__(256) void sta_bwd_delta_kernel(const uint4 *__restr
 // ---------------------------------------------------------------------------------------------------------
 // dQ.  grid = (N / 128, B * heads).  LDS stage: K (read by rows and transposed) and V (read by rows).
 // ---------------------------------------------------------------------------------------------------------
+template <int STAGES>
 __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw *__restrict__ q,
                                                                  const bf16_raw *__restrict__ k,
                                                                  const bf16_raw *__restrict__ v,
@@ -236,7 +237,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
 {
     constexpr int OPS = 2, STAGE_B = OPS * kTileB;
     constexpr int K_TILE = 0, V_TILE = kTileB;
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
+    __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_B];
+    static_assert(STAGES * STAGE_B <= 65536, "operand reads carry the stage as a 16-bit immediate offset");
 
     const uint32_t qblock = blockIdx.x;
     const uint32_t heads = p.heads;
@@ -288,19 +290,23 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
     BoxWalk walk;
     walk.start(box, p.n_h, p.n_w, p.P);
     const int n_iter = box.count() * walk.sub_per_tile;
-    int issued = 0;
+    // Up to STAGES - 1 sub-blocks are in flight; each is 4 DMA instructions per wave, returned in order.
+    int issued = 0, dma_stage = 0;
     auto issue_next = [&]() {
         if (issued < n_iter) {
-            issue_loads(issued & 1, walk.next_row);
+            issue_loads(dma_stage, walk.next_row);
+            dma_stage = dma_stage == STAGES - 1 ? 0 : dma_stage + 1;
             walk.advance();
             ++issued;
         }
     };
-    issue_next();
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue_next();
 
-    auto sub_block = [&](auto stage_c) {
+    auto sub_block = [&](auto stage_c, int iter) {
         constexpr int ST = decltype(stage_c)::value * STAGE_B;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (STAGES == 2 || issued - 1 - iter == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         __syncthreads();
         issue_next();
         const floatx16 S = rows_times_resident<ST + K_TILE>(row_addr, Qr);     // S^T  = K Q^T   (keys x queries)
@@ -317,9 +323,10 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
         pack16(ds, dSb);
         k_t.run(tr_addr, dSb, dQ);                                              // dQ^T += K^T dS^T
     };
-    for (int iter = 0; iter < n_iter; iter += 2) {
-        sub_block(std::integral_constant<int, 0>{});
-        if (iter + 1 < n_iter) sub_block(std::integral_constant<int, 1>{});
+    for (int iter = 0; iter < n_iter; iter += STAGES) {
+        static_for<0, STAGES>([&](auto st) {
+            if (iter + decltype(st)::value < n_iter) sub_block(st, iter + decltype(st)::value);
+        });
     }
     store_columns(d_q + my_row * kD, lane, dQ, c * kLn2);
 }
@@ -490,7 +497,7 @@ hipError_t launch_backward(const void *q, const void *k, const void *v, const vo
         if (e != hipSuccess) return e;
     }
     dim3 grid(p.N / kCols, (uint32_t)B * p.heads), block(kNW * 64);
-    sta_bwd_dq_kernel<<<grid, block, 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_q), p, win);
+    sta_bwd_dq_kernel<2><<<grid, block, 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_q), p, win);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     sta_bwd_dkv_kernel<<<grid, dim3(512), 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_k),
