@@ -47,6 +47,7 @@ def parse_args():
     ap.add_argument("--window", default=None, help="override: uniform window in tiles, e.g. 3,3,3")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense (full-window) comparison run")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-backward", action="store_true", help="skip the gradient entry point's timing")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line, time sta_forward for a list of uniform windows and the "
@@ -323,6 +324,34 @@ def main():
             "ms": dense_ms, "tflops": dense_flops / (dense_ms * 1e-3) / 1e12,
             "speedup_sparse_vs_dense": dense_ms / fwd_ms, "ideal_speedup": dense_flops / flops,
             "kernel_efficiency": (flops / fwd_ms) / (dense_flops / dense_ms),
+        }
+
+    # What the matrix pipes deliver on this chip, this run, for the attention kernels' MFMA instruction alone:
+    # with constant operands (little switching, the clock stays high) and with N(0,1) bf16 operands.
+    sink = torch.empty(512 * 256, dtype=torch.float32, device=device)
+    probe = {}
+    for label, operands in (("constant_operands", torch.ones(8192, dtype=torch.bfloat16, device=device)),
+                            ("random_operands", layer.q.reshape(-1)[:8192].contiguous())):
+        probe_flops = sta.sta_probe_mfma(operands, 10000, 512, sink)
+        probe_ms = event_time_ms(lambda: sta.sta_probe_mfma(operands, 10000, 512, sink), 3)
+        probe[label + "_tflops"] = probe_flops / (probe_ms * 1e-3) / 1e12
+    probe["sta_forward_frac_of_random_operand_rate"] = fwd_tflops / probe["random_operands_tflops"]
+    probe["what"] = ("v_mfma_f32_32x32x16_bf16 only, 2 waves per SIMD on all CUs, no memory traffic; the nominal "
+                     "peak in `roofline` assumes 2.4 GHz, which the chip does not hold on random data")
+    out["mfma_probe"] = probe
+
+    if not args.no_backward and w.D == 128 and w.P % 128 == 0:
+        lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=device)
+        sta.sta_forward_lse(layer.qt, layer.kt, layer.vt, layer.ot, lse, w.grid, w.tile, w.window_tiles)
+        bws = torch.empty(sta.sta_backward_workspace_bytes(w.B, w.H, w.grid), dtype=torch.uint8, device=device)
+        # dO: any N(0,1) bf16 tensor of the right shape; the raster inputs are not needed any more and hold the outputs
+        bwd_ms = event_time_ms(lambda: sta.sta_backward(layer.qt, layer.kt, layer.vt, layer.ot, layer.q, lse, layer.k,
+                                                        layer.v, layer.o, w.grid, w.tile, w.window_tiles, bws), 3)
+        out["backward"] = {
+            "sta_backward_ms": bwd_ms, "matrix_products_needed": 5, "matrix_products_executed": 7,
+            "tflops_needed": 2.5 * flops / (bwd_ms * 1e-3) / 1e12,
+            "tflops_executed": 3.5 * flops / (bwd_ms * 1e-3) / 1e12,
+            "frac_of_peak_executed": 3.5 * flops / (bwd_ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
         }
 
     if not args.no_cpu:
