@@ -331,7 +331,7 @@ def main():
     sink = torch.empty(512 * 256, dtype=torch.float32, device=device)
     probe = {}
     for label, operands in (("constant_operands", torch.ones(8192, dtype=torch.bfloat16, device=device)),
-                            ("random_operands", layer.q.reshape(-1)[:8192].contiguous())):
+                            ("random_operands", layer.qt.reshape(-1)[:8192].contiguous())):
         probe_flops = sta.sta_probe_mfma(operands, 10000, 512, sink)
         probe_ms = event_time_ms(lambda: sta.sta_probe_mfma(operands, 10000, 512, sink), 3)
         probe[label + "_tflops"] = probe_flops / (probe_ms * 1e-3) / 1e12
