@@ -246,15 +246,15 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
 
 
 // ---------------------------------------------------------------------------
-// Fast path: head dim 128, 128 queries per workgroup (4 waves x 32 queries),
-// two workgroups per CU (two waves per SIMD, so one wave's softmax overlaps the
-// other's MFMAs), K/V sub-blocks of KB keys DMA'd HBM/L2 -> LDS with
-// global_load_lds (no staging registers), double-buffered, one barrier per
-// sub-block.  LDS holds K and V row-major, 256 B per key, with the 16-byte
-// chunks of each row XOR-swizzled so that both the b128 K-operand reads and the
-// transposing ds_read_b64_tr_b16 V-operand reads are bank-conflict free:
+// Fast path: head dim 128.  NW waves x 32 queries per workgroup (one query block per wave; at least two waves
+// per SIMD on a CU, so one wave's softmax overlaps another's MFMAs), K/V sub-blocks of KB keys DMA'd
+// HBM/L2 -> LDS with global_load_lds (no staging registers), STAGES-deep, one barrier per sub-block.  LDS holds
+// K and V row-major, 256 B per key, with the 16-byte chunks of each row XOR-swizzled so that both the b128
+// K-operand reads and the transposing ds_read_b64_tr_b16 V-operand reads are bank-conflict free:
 //   K: chunk c of row r is stored at chunk position c ^ (r & 15)
 //   V: chunk c of row r is stored at chunk position c ^ ((r & 3) << 2)
+// Instances in use: <12, 32, 2, 1> (384-token tiles: one 12-wave workgroup per query tile and per CU) and
+// <4, 64, 2, 2> (other tile sizes that are multiples of 128: two 4-wave workgroups per CU).
 // ---------------------------------------------------------------------------
 template <int NW, int KB, int STAGES, int MINB>
 __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_raw *__restrict__ q,
