@@ -90,6 +90,20 @@ def test_backward_parity_whole(name, B, H, grid, tile, windows, scale):
                 print(name, label, b, h, st)
 
 
+def test_backward_many_heads_in_chunks():
+    """More heads than one launch carries (256): the entry point launches in chunks; windows differ per head."""
+    H = 260
+    windows = [((1, 1, 1), (1, 1, 3), (3, 3, 3))[h % 3] for h in range(H)]
+    w = syn.custom("bwd-manyheads", 1, H, 128, (2, 8, 32), (2, 8, 8), windows, "bf16", seed=1204)
+    q, k, v = syn.make_qkv(w)
+    g = syn.make_dout(w)
+    (dq, dk, dv), _ = gpu_backward(w, q, k, v, g)
+    for h in (0, 1, 254, 255, 256, 257, 259):
+        rq, rk, rv = oracle_backward(w, q, k, v, g, 0, h)
+        for label, got, ref in (("dQ", dq, rq), ("dK", dk, rk), ("dV", dv, rv)):
+            assert_grad_parity(got[0, h].float().numpy(), ref, "manyheads %s h%d" % (label, h))
+
+
 def test_backward_is_bit_reproducible():
     w = syn.custom("bwd-repro", 1, 2, 128, (4, 16, 16), (2, 8, 8), [(3, 3, 1), (1, 1, 3)], "bf16", seed=1202)
     q, k, v = syn.make_qkv(w)
