@@ -371,23 +371,40 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
 
     const int sub_per_tile = p.P / KB;
     const int n_iter = box.count() * sub_per_tile;
-    int it_t = box.t.lo, it_h = box.h.lo, it_w = box.w.lo, it_s = 0;
+    // Order in which the key tiles of the box are visited.  Along each axis the box [lo, hi] holds e = hi-lo+1
+    // consecutive tiles, hence exactly one tile of every residue class mod e; the walk takes them in the order
+    // of that residue (k mod e = 0, 1, ..), i.e. it starts inside the box and wraps from hi to lo.  Query tiles
+    // that are neighbours along an axis have boxes shifted by one tile: with this order they reach each key
+    // tile they share at the SAME step of their walks, so workgroups resident on an XCD at one time read the
+    // same K/V tiles at about the same time and find them in that XCD's L2.  (Walking every box from its own lo
+    // makes neighbours read a shared tile at different steps; the L2 is far too small to keep it that long.)
+    const int e_t = box.t.hi - box.t.lo + 1, e_h = box.h.hi - box.h.lo + 1, e_w = box.w.hi - box.w.lo + 1;
+    const int start_t = box.t.lo + (e_t - box.t.lo % e_t) % e_t;
+    const int start_h = box.h.lo + (e_h - box.h.lo % e_h) % e_h;
+    const int start_w = box.w.lo + (e_w - box.w.lo % e_w) % e_w;
+    int it_t = start_t, it_h = start_h, it_w = start_w, it_s = 0;
+    int left_h = e_h, left_w = e_w;         // tiles still to visit in the current h-cycle / w-cycle
     auto row_start = [&]() -> size_t {      // byte offset of key tile (it_t, it_h, it_w) inside the head
         const size_t kt = ((size_t)it_t * p.n_h + it_h) * p.n_w + it_w;
         return kt * p.P * ROWB;
     };
-    // Key tiles that are neighbours along w are neighbours in memory, so the offset simply keeps growing by one
-    // sub-block until the walk wraps to the next row of the box.
     size_t next_base = row_start();
     auto advance = [&]() {
         next_base += (size_t)KB * ROWB;
         if (++it_s == sub_per_tile) {
             it_s = 0;
-            if (++it_w > box.w.hi) {
-                it_w = box.w.lo;
-                if (++it_h > box.h.hi) { it_h = box.h.lo; ++it_t; }
-                next_base = row_start();
+            if (++it_w > box.w.hi) it_w = box.w.lo;
+            if (--left_w == 0) {
+                left_w = e_w;
+                it_w = start_w;
+                if (++it_h > box.h.hi) it_h = box.h.lo;
+                if (--left_h == 0) {
+                    left_h = e_h;
+                    it_h = start_h;
+                    if (++it_t > box.t.hi) it_t = box.t.lo;
+                }
             }
+            next_base = row_start();
         }
     };
 

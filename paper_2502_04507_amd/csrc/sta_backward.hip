@@ -127,17 +127,29 @@ __device__ __forceinline__ void pack16(const float (&x)[16], bf16x8 (&out)[2])
         for (int e = 0; e < 8; ++e) out[j][e] = static_cast<__bf16>(x[8 * j + e]);
 }
 
-// Walks the sub-blocks of the tiles of a box in ascending tile order; row() is the first token row (tiled
-// order, inside the head) of the sub-block to request next.
+// Walks the sub-blocks of the tiles of a box; next_row is the first token row (tiled order, inside the head) of
+// the sub-block to request next.  Along each axis the box [lo, hi] holds e = hi-lo+1 consecutive tiles, hence
+// one tile of every residue class mod e; they are taken in the order of that residue, i.e. the walk starts
+// inside the box and wraps from hi to lo.  Neighbouring workgroups, whose boxes are shifted by one tile, then
+// reach the tiles they share at the same step of their walks and find them in their XCD's L2.
 struct BoxWalk {
     StaBox box;
     int n_h, n_w, P, sub_per_tile;
+    int e_h, e_w, start_h, start_w, left_h, left_w;
     int t, h, w, s;
     uint32_t next_row;
+    __device__ __forceinline__ static int first_of(const StaAxisRange &r)      // the tile of the box with k mod e == 0
+    {
+        const int e = r.hi - r.lo + 1;
+        return r.lo + (e - r.lo % e) % e;
+    }
     __device__ __forceinline__ void start(const StaBox &b, int nh, int nw, int tokens_per_tile)
     {
         box = b; n_h = nh; n_w = nw; P = tokens_per_tile; sub_per_tile = tokens_per_tile / kSub;
-        t = b.t.lo; h = b.h.lo; w = b.w.lo; s = 0;
+        e_h = b.h.hi - b.h.lo + 1; e_w = b.w.hi - b.w.lo + 1;
+        start_h = first_of(b.h); start_w = first_of(b.w);
+        t = first_of(b.t); h = start_h; w = start_w; s = 0;
+        left_h = e_h; left_w = e_w;
         next_row = tile_row();
     }
     __device__ __forceinline__ uint32_t tile_row() const { return (uint32_t)(((t * n_h + h) * n_w + w) * P); }
@@ -146,14 +158,37 @@ struct BoxWalk {
         next_row += kSub;
         if (++s == sub_per_tile) {
             s = 0;
-            if (++w > box.w.hi) {
-                w = box.w.lo;
-                if (++h > box.h.hi) { h = box.h.lo; ++t; }
-                next_row = tile_row();
+            if (++w > box.w.hi) w = box.w.lo;
+            if (--left_w == 0) {
+                left_w = e_w;
+                w = start_w;
+                if (++h > box.h.hi) h = box.h.lo;
+                if (--left_h == 0) {
+                    left_h = e_h;
+                    h = start_h;
+                    if (++t > box.t.hi) t = box.t.lo;
+                }
             }
+            next_row = tile_row();
         }
     }
 };
+
+// Work item of a workgroup.  The hardware deals workgroup ids round-robin over the 8 XCDs (each with its own
+// L2).  The launch's column blocks, taken head after head, are cut into chunks of `chunk` consecutive blocks and
+// the chunks are dealt to the XCDs in turn: the blocks resident on one XCD at a time are then neighbours that
+// share most of their windows, while all XCDs together still work on one region of one head.
+// Returns false for the padding ids of the launch.
+__device__ __forceinline__ bool work_item(uint32_t chunk, uint32_t blocks_per_head, uint32_t n_bh, uint32_t *block,
+                                          uint32_t *bh_rank)
+{
+    const uint32_t xcd = blockIdx.x & 7, s = blockIdx.x >> 3;
+    const uint32_t linear = ((s / chunk) * 8 + xcd) * chunk + s % chunk;
+    if (linear >= blocks_per_head * n_bh) return false;
+    *bh_rank = linear / blocks_per_head;
+    *block = linear - *bh_rank * blocks_per_head;
+    return true;
+}
 
 // Per-lane constants of the operand reads (relative to the start of a staged sub-block).
 //  Row reads: row lo, logical chunk 2*ks + hb.
@@ -223,7 +258,7 @@ __global__ __launch_bounds__(256) void sta_bwd_delta_kernel(const uint4 *__restr
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// dQ.  grid = (N / 128, B * heads).  LDS stage: K (read by rows and transposed) and V (read by rows).
+// dQ.  One workgroup per 128 queries.  LDS stage: K (read by rows and transposed) and V (read by rows).
 // ---------------------------------------------------------------------------------------------------------
 template <int STAGES>
 __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw *__restrict__ q,
@@ -233,16 +268,17 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
                                                                  const float *__restrict__ lse,
                                                                  const float *__restrict__ delta,
                                                                  bf16_raw *__restrict__ d_q, sta::FwdParams p,
-                                                                 sta::WindowTable win)
+                                                                 sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
 {
     constexpr int OPS = 2, STAGE_B = OPS * kTileB;
     constexpr int K_TILE = 0, V_TILE = kTileB;
     __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_B];
     static_assert(STAGES * STAGE_B <= 65536, "operand reads carry the stage as a 16-bit immediate offset");
 
-    const uint32_t qblock = blockIdx.x;
+    uint32_t qblock, bh_rank;
+    if (!work_item(chunk, p.N / kCols, n_bh, &qblock, &bh_rank)) return;
     const uint32_t heads = p.heads;
-    const uint32_t h_local = blockIdx.y % heads, b = blockIdx.y / heads;
+    const uint32_t h_local = bh_rank % heads, b = bh_rank / heads;
     const size_t bh = (size_t)b * p.H + p.head_base + h_local;
     const uint32_t q_tile = (qblock * kCols) / p.P;
     const StaBox box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1], win.w[h_local][2],
@@ -332,7 +368,7 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// dK, dV.  grid = (N / 128, B * heads), 8 waves.  LDS stage: Q and dO (each read by rows and transposed).
+// dK, dV.  One workgroup of 8 waves per 128 keys.  LDS stage: Q and dO (each read by rows and transposed).
 // The four 32-key column blocks of the workgroup are each served by a PAIR of waves (w and w + 4, which
 // share a SIMD): wave w holds K and accumulates dV (S = Q K^T, P, dV^T += dO^T P), wave w + 4 holds V and
 // accumulates dK (dP = dO V^T, dS = P o (dP - delta), dK^T += Q^T dS).  P, rounded to bf16 and packed as the
@@ -352,16 +388,17 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
                                                              const float *__restrict__ delta,
                                                              bf16_raw *__restrict__ d_k,
                                                              bf16_raw *__restrict__ d_v, sta::FwdParams p,
-                                                             sta::WindowTable win)
+                                                             sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
 {
     constexpr int OPS = 2, STAGE_B = OPS * kTileB;
     constexpr int Q_TILE = 0, G_TILE = kTileB;
     constexpr int P_XCHG = 2 * STAGE_B;                 // 4 column blocks x 2 planes x 64 lanes x 16 B
     __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 4 * 2048];
 
-    const uint32_t kblock = blockIdx.x;
+    uint32_t kblock, bh_rank;
+    if (!work_item(chunk, p.N / kCols, n_bh, &kblock, &bh_rank)) return;
     const uint32_t heads = p.heads;
-    const uint32_t h_local = blockIdx.y % heads, b = blockIdx.y / heads;
+    const uint32_t h_local = bh_rank % heads, b = bh_rank / heads;
     const size_t bh = (size_t)b * p.H + p.head_base + h_local;
     const uint32_t k_tile = (kblock * kCols) / p.P;
     const StaBox box = sta_query_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1],
@@ -496,12 +533,19 @@ hipError_t launch_backward(const void *q, const void *k, const void *v, const vo
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    dim3 grid(p.N / kCols, (uint32_t)B * p.heads), block(kNW * 64);
-    sta_bwd_dq_kernel<2><<<grid, block, 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_q), p, win);
+    const uint32_t n_bh = (uint32_t)B * p.heads;
+    const uint32_t total = (p.N / kCols) * n_bh;
+    auto grid_for = [&](uint32_t chunk) { return dim3(8 * chunk * ((((total + chunk - 1) / chunk) + 7) / 8)); };
+    // One chunk = the column blocks of one row of tiles along w.  Measured at the 30x48x80 grid (chunk sizes 1, 3,
+    // 6, 30, 60, 120 in one session): dK/dV kernel 32.7, 31.5, 31.6, 31.0, 31.1, 34.0 ms; dQ kernel 18.9, 18.8, 18.7,
+    // 18.5, 18.5, 19.3 ms.
+    const uint32_t chunk = p.n_w * (p.P / kCols);
+    dim3 block(kNW * 64);
+    sta_bwd_dq_kernel<2><<<grid_for(chunk), block, 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_q), p, win, n_bh, chunk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    sta_bwd_dkv_kernel<<<grid, dim3(512), 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_k),
-                                                   static_cast<bf16_raw *>(d_v), p, win);
+    sta_bwd_dkv_kernel<<<grid_for(chunk), dim3(512), 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_k),
+                                                   static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk);
     return hipGetLastError();
 }
 
