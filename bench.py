@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0
 # same counter reads for a plain copy of known size (FETCH_SIZE x2.0, WRITE_SIZE x1.0 on this machine); summary in
 # profiles/sta_forward_C4_w3x3x3_pmc.txt.  Only workloads that were actually profiled have an entry.
 MEASURED_FORWARD_TRAFFIC_BYTES = {
-    ("C4", ((3, 3, 3),)): 9.85e9 + 0.708e9,
+    ("C4", ((3, 3, 3),)): 6.39e9 + 0.708e9,
 }
 
 

@@ -296,7 +296,24 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     if (seg_len == 0) return;
     const uint32_t bh_rank = slot / seg_len;
     if (bh_rank >= n_bh) return;
-    const uint32_t qblock = seg_lo + (slot - bh_rank * seg_len);
+    // Position in the head's scheduling order -> query block.  The query tiles of a head are scheduled by pairs of
+    // tile rows (h), then w, then the row of the pair, then t fastest, so that the ~32 tiles resident on an XCD at
+    // one time form a compact 3-D block, (all t) x (2 h) x (about 3 w), and share key tiles along all three axes
+    // (measured: reads past L2 9.8 -> 6.4 GB per launch against plain tile-id order, 12.81 -> 12.74 ms).
+    uint32_t qblock;
+    {
+        const uint32_t pos = seg_lo + (slot - bh_rank * seg_len);
+        const uint32_t per_tile = p.P / QB;
+        const uint32_t sched = pos / per_tile, sub = pos - sched * per_tile;
+        const uint32_t pair_items = 2 * p.n_w * p.n_t;
+        const uint32_t hp = sched / pair_items;
+        uint32_t rem = sched - hp * pair_items;
+        const uint32_t rows = (p.n_h - 2 * hp) < 2 ? (p.n_h - 2 * hp) : 2;
+        const uint32_t w_ = rem / (rows * p.n_t);
+        rem -= w_ * rows * p.n_t;
+        const uint32_t hh = rem / p.n_t, t_ = rem - hh * p.n_t;
+        qblock = ((t_ * p.n_h + 2 * hp + hh) * p.n_w + w_) * per_tile + sub;
+    }
     const uint32_t h_local = order.h[bh_rank / (n_bh / p.heads)];     // batch entries of one head are adjacent
     const uint32_t b = bh_rank % (n_bh / p.heads);
     const size_t bh = (size_t)b * p.H + p.head_base + h_local;
