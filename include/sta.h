@@ -140,6 +140,19 @@ int sta_head_mse(const void *a, const void *b, int B, int H, int D,
                  float *dev_mse, void *hip_stream);
 
 /*
+ * sta_head_mse for callers that cannot allocate or pass device scratch: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels, summation order and
+ * result bits as sta_head_mse, but the partial sums go to a fixed 512 KB array inside the library's
+ * device image (one copy per GPU, held until the process ends) instead of a workspace; the call itself
+ * allocates and frees nothing.  Limit: B * H <= 1024, else STA_ERR_WORKSPACE.  Every partial sum the
+ * second kernel reads is written by the first one in the same call, so nothing needs clearing between
+ * calls; but all calls on one GPU share the array, so two calls that may overlap in time on the same GPU
+ * (different streams) race and must be ordered by the caller.
+ */
+int sta_head_mse_static(const void *a, const void *b, int B, int H, int D,
+                        const int grid[3], float *dev_mse, void *hip_stream);
+
+/*
  * Inner loop of the paper's mask-search algorithm for one layer and one set of
  * activations: O <- full attention; for every pattern p of the list (window
  * sizes in tiles, host, [n_patterns][3]): O' <- STA with window p, loss <-

@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = (
     "sta_tile_permute", "sta_untile", "sta_forward", "sta_forward_lse", "sta_workspace_bytes", "sta_key_tile_box",
     "sta_dump_key_tiles", "sta_window_tokens_to_tiles", "sta_kept_flops", "sta_strerror", "sta_version",
     "sta_head_mse_workspace_bytes", "sta_head_mse", "sta_mask_search", "sta_attention_recall", "sta_block_census",
-    "sta_backward_workspace_bytes", "sta_backward", "sta_query_tile_box", "sta_probe_mfma",
+    "sta_backward_workspace_bytes", "sta_backward", "sta_query_tile_box", "sta_probe_mfma", "sta_head_mse_static",
 )
 
 
@@ -57,6 +57,8 @@ def load_library():
     lib.sta_head_mse_workspace_bytes.restype = ctypes.c_size_t
     lib.sta_head_mse.argtypes = [vp, vp, ci, ci, ci, _I3, vp, ctypes.c_size_t, vp, vp]
     lib.sta_head_mse.restype = ci
+    lib.sta_head_mse_static.argtypes = [vp, vp, ci, ci, ci, _I3, vp, vp]
+    lib.sta_head_mse_static.restype = ci
     lib.sta_mask_search.argtypes = [vp, vp, vp, ci, ci, ci, _I3, _I3, ctypes.POINTER(ci), ci, cf, vp, vp, vp,
                                     ctypes.c_size_t, vp, vp, vp]
     lib.sta_mask_search.restype = ci
@@ -311,6 +313,18 @@ def sta_head_mse(a, b, grid, workspace, mse, stream=None):
         raise ValueError("mse must be float32 [H]")
     _check(load_library().sta_head_mse(_dev(a, "a"), _dev(b, "b"), B, H, D, _i3(grid), _dev(workspace, "workspace"),
                                        _nbytes(workspace), _dev(mse, "mse"), _stream_ptr(stream)))
+    return mse
+
+
+def sta_head_mse_static(a, b, grid, mse, stream=None):
+    """sta_head_mse without a workspace argument (partial sums in a fixed device array of the library)."""
+    if a.shape != b.shape or a.dtype != torch.bfloat16 or b.dtype != torch.bfloat16 or a.dim() != 4:
+        raise ValueError("expect two bf16 [B, H, N, D] tensors of equal shape")
+    B, H, N, D = a.shape
+    if mse.dtype != torch.float32 or mse.numel() != H:
+        raise ValueError("mse must be float32 [H]")
+    _check(load_library().sta_head_mse_static(_dev(a, "a"), _dev(b, "b"), B, H, D, _i3(grid), _dev(mse, "mse"),
+                                              _stream_ptr(stream)))
     return mse
 
 

@@ -313,6 +313,22 @@ int sta_head_mse(const void *a, const void *b, int B, int H, int D, const int gr
     return e == hipSuccess ? STA_OK : STA_ERR_HIP;
 }
 
+int sta_head_mse_static(const void *a, const void *b, int B, int H, int D, const int grid[3], float *dev_mse,
+                        void *hip_stream)
+{
+    if (!a || !b || !dev_mse) return STA_ERR_NULL;
+    const int unit[3] = {1, 1, 1};
+    Shape s;
+    if (int rc = check_shape(B, H, D, grid, unit, &s)) return rc;
+    if (D % 8 != 0) return STA_ERR_UNSUPPORTED;
+    if ((int64_t)B * H > sta::kStaticMseMaxSlabs) return STA_ERR_WORKSPACE;
+    double *partial = nullptr;
+    if (sta::static_mse_scratch(&partial) != hipSuccess) return STA_ERR_HIP;
+    hipError_t e = sta::launch_head_mse(a, b, B, H, (size_t)s.N * D, partial, dev_mse,
+                                        static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? STA_OK : STA_ERR_HIP;
+}
+
 int sta_attention_recall(const float *lse_window, const float *lse_full, int B, int H, const int grid[3],
                          void *workspace, size_t workspace_bytes, float *dev_recall, float *dev_mean,
                          void *hip_stream)

@@ -63,6 +63,10 @@ bool backward_supported(int P, int D);
 constexpr int kMseSlices = 64;     // partial sums per (batch, head) slab
 hipError_t launch_head_mse(const void *a, const void *b, int B, int H, size_t elems_per_head, double *partial,
                            float *mse_per_head, hipStream_t stream);
+// Allocation-free variant: the partial sums live in a file-scope device array of kStaticMseMaxSlabs * kMseSlices
+// doubles.  static_mse_scratch returns the current device's address of that array (looked up once per device).
+constexpr int kStaticMseMaxSlabs = 1024;
+hipError_t static_mse_scratch(double **out);
 hipError_t launch_first_min(const float *losses, int n_patterns, int H, int32_t *best, hipStream_t stream);
 hipError_t launch_recall(const float *lse_window, const float *lse_full, int BH, size_t N, float *recall,
                          double *partial, float *mean_bh, hipStream_t stream);

@@ -8,11 +8,20 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "sta_internal.h"
 
 namespace {
 
 constexpr int kThreads = 256;
+
+// Partial sums of the allocation-free per-head MSE entry point: kMseSlices doubles per (batch, head) slab, for
+// at most kStaticMseMaxSlabs slabs (512 KB).  Every GPU the library runs on holds its own copy at its own
+// address until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; kernels
+// receive the device address that call returns.
+static __device__ __align__(256) double scratch[sta::kStaticMseMaxSlabs * sta::kMseSlices];
+constexpr int kMaxDevices = 64;
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -174,6 +183,26 @@ hipError_t launch_head_mse(const void *a, const void *b, int B, int H, size_t el
                                                                         1.0 / ((double)B * (double)elems_per_head),
                                                                         mse_per_head);
     return hipGetLastError();
+}
+
+hipError_t static_mse_scratch(double **out)
+{
+    static std::mutex mu;
+    static double *per_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (per_device[dev] == nullptr) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (ptr == nullptr) return hipErrorInvalidSymbol;
+        per_device[dev] = static_cast<double *>(ptr);
+    }
+    *out = per_device[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_first_min(const float *losses, int n_patterns, int H, int32_t *best, hipStream_t stream)
