@@ -273,9 +273,9 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     constexpr int TILE_BYTES = KB * ROWB;          // one K (or V) sub-block
     constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // K then V
     constexpr int INSTR = TILE_BYTES / 1024;       // 1 KB DMA instructions per operand per sub-block
-    constexpr int LOADS = INSTR / NW > 0 ? INSTR / NW : 1;   // ... issued by each loading wave
-    constexpr int LOADERS = INSTR / LOADS;         // waves 0 .. LOADERS-1 issue the DMA
-    static_assert(KB % 32 == 0 && INSTR % LOADS == 0 && LOADERS <= NW, "sub-block shape");
+    constexpr int LOADERS = NW < 8 ? 4 : 8;        // waves 0 .. LOADERS-1 issue the DMA
+    constexpr int LOADS = INSTR / LOADERS;         // ... this many instructions per operand each
+    static_assert(KB % 32 == 0 && INSTR % LOADERS == 0 && LOADS >= 1 && LOADERS <= NW, "sub-block shape");
     static_assert(STAGES >= 2 && STAGES <= 4, "LDS stages");
 
     __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_BYTES];
@@ -331,29 +331,33 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     const char *kh = reinterpret_cast<const char *>(k + bh * p.N * D);
     const char *vh = reinterpret_cast<const char *>(v + bh * p.N * D);
 
-    // ---- per-lane constants of the DMA loads: each wave-wide 16 B/lane instruction fills 1 KB = 4 key rows;
-    // instruction i of this wave fills rows ROWS_PER_WAVE*wave + 4*i + (lane>>4).  A lane's LDS slot is
-    // fixed by the hardware (base + 16*lane), so the swizzle is applied on the global side: the lane
-    // fetches the logical chunk that belongs at its slot.
-    constexpr int ROWS_PER_WAVE = LOADS * 4;
-    uint32_t k_goff[LOADS], v_goff[LOADS];
-#pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-        const int row = ROWS_PER_WAVE * wave + 4 * i + (lane >> 4);
+    // ---- DMA loads.  Each wave-wide 16 B/lane instruction fills 1 KB of LDS = 4 consecutive key rows (a lane's
+    // LDS slot is fixed by the hardware: base + 16*lane), so the swizzle is applied on the global side: the lane
+    // fetches the logical chunk that belongs at its slot.  The KB keys of a sub-block are taken as blocks of 16
+    // rows; loading wave w fetches rows 4*(w&3) .. +3 of the blocks LOADS*(w>>2) .. +LOADS-1, one instruction per
+    // block.  Both swizzles depend on the row only through row & 15, so a lane's offset inside its block is the
+    // same for all its instructions and the rest of the address is wave-uniform: one 32-bit lane offset per
+    // operand on top of a scalar base, and no vector arithmetic per load.
+    uint32_t k_lane_off, v_lane_off;
+    {
+        const int lrow = 4 * (wave & 3) + (lane >> 4);      // row & 15 of every row this lane fetches
         const int slot = lane & 15;
-        k_goff[i] = (uint32_t)(row * ROWB + ((slot ^ (row & 15)) << 4));
-        v_goff[i] = (uint32_t)(row * ROWB + ((slot ^ ((row & 3) << 2)) << 4));
+        k_lane_off = (uint32_t)(lrow * ROWB + ((slot ^ lrow) << 4));
+        v_lane_off = (uint32_t)(lrow * ROWB + ((slot ^ ((lrow & 3) << 2)) << 4));
     }
-
     auto issue_loads = [&](int stage, size_t key_byte_base) {
-        char *kdst = smem + stage * STAGE_BYTES + wave * (LOADS * 1024);   // only waves < LOADERS get here
-        char *vdst = kdst + TILE_BYTES;
+        char *sdst = smem + stage * STAGE_BYTES;                           // only waves < LOADERS get here
+        uint32_t koff = k_lane_off, voff = v_lane_off;
+        asm volatile("" : "+v"(koff), "+v"(voff));      // keep the lane offsets 32-bit next to a scalar base
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + key_byte_base + k_goff[i]),
-                                             STA_LDS_PTR(kdst + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + key_byte_base + v_goff[i]),
-                                             STA_LDS_PTR(vdst + i * 1024), 16, 0, 0);
+            const int block16 = LOADS * (wave >> 2) + i;
+            const size_t gbase = key_byte_base + (size_t)block16 * (16 * ROWB);
+            char *kdst = sdst + (16 * block16 + 4 * (wave & 3)) * ROWB;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + gbase + koff),
+                                             STA_LDS_PTR(kdst), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + gbase + voff),
+                                             STA_LDS_PTR(kdst + TILE_BYTES), 16, 0, 0);
         }
     };
 
@@ -426,6 +430,15 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     };
 
     const float c = p.scale_log2e;
+    // The SIMD's arbiter prefers its oldest wave, and a wave whose next instruction is an MFMA waiting for the
+    // matrix pipe holds the vector issue port meanwhile: the softmax arithmetic of the younger waves of a SIMD
+    // then waits behind the older waves' matrix phases.  Static priorities against the age order (waves w, w+4,
+    // w+8 share a SIMD) even this out.  Measured in one call: 12.41 -> 12.22 ms, and 9.50 -> 9.24 ms on constant
+    // inputs, where the clock does not move.
+    if constexpr (NW == 12) {
+        if (wave >= 8) __builtin_amdgcn_s_setprio(2);
+        else if (wave >= 4) __builtin_amdgcn_s_setprio(1);
+    }
 
     // ---- pipeline: up to STAGES-1 sub-blocks are in flight.  (it_t, it_h, it_w, it_s) always names the next
     // sub-block to request; `issued` counts the requests made so far.
