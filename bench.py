@@ -67,13 +67,17 @@ def parse_args():
 class Layer:
     """Device buffers of one attention layer call and the calls of the path."""
 
-    def __init__(self, w, device):
+    def __init__(self, w, device, split=True):
         self.w = w
+        self.split = split
         self.q, self.k, self.v = syn.make_qkv_device(w, device)      # raster inputs, resident in HBM
         shape = self.q.shape
         mk = lambda: torch.empty(shape, dtype=torch.bfloat16, device=device)
         self.qt, self.kt, self.vt, self.ot, self.o = mk(), mk(), mk(), mk(), mk()
         self.windows = w.window_tiles
+        # scratch with which sta_forward splits the work items of the ragged last round of workgroups
+        self.ws = torch.empty(max(sta.sta_workspace_bytes(w.B, w.H, w.D, w.grid, w.tile), 16), dtype=torch.uint8,
+                              device=device)
 
     def permute_in(self):
         w = self.w
@@ -83,7 +87,8 @@ class Layer:
 
     def forward(self, windows=None):
         w = self.w
-        sta.sta_forward(self.qt, self.kt, self.vt, self.ot, w.grid, w.tile, windows or self.windows)
+        sta.sta_forward(self.qt, self.kt, self.vt, self.ot, w.grid, w.tile, windows or self.windows,
+                        workspace=self.ws if self.split else None)
 
     def untile(self):
         sta.sta_untile(self.ot, self.o, self.w.grid, self.w.tile)

@@ -75,8 +75,18 @@ int sta_untile(const void *src, void *dst, int src_dt, int dst_dt,
  * scores, softmax statistics and output accumulator, probabilities rounded
  * to bf16 before the PV product, output rounded to bf16.
  * Supported: D in {64, 128}; P a multiple of 32.  Anything else returns
- * STA_ERR_UNSUPPORTED.  workspace: device scratch of at least
- * sta_workspace_bytes(...) bytes (may be NULL when that is 0).
+ * STA_ERR_UNSUPPORTED.
+ * workspace: optional device scratch, 16-byte aligned, of at least
+ * sta_workspace_bytes(...) bytes.  With it, the work items that would make up
+ * the ragged last round of workgroups (the number of query tiles is rarely a
+ * multiple of what the chip holds at once) are cut along the keys into parts
+ * that fill the chip, each part leaving an unnormalised accumulator, exponent
+ * offset and row sum there, and a second kernel merges them in a fixed order
+ * (results stay repeatable bit for bit; they differ from the unsplit run by
+ * rounding only).  NULL: every query tile is computed by one workgroup.  A
+ * non-NULL workspace that is too small or misaligned is STA_ERR_WORKSPACE; one
+ * that overlaps a tensor is STA_ERR_ALIAS.  Its contents are undefined after
+ * the call.
  */
 int sta_forward(const void *q_tiled, const void *k_tiled, const void *v_tiled,
                 void *o_tiled, int B, int H, int D, const int grid[3],
@@ -185,7 +195,8 @@ int sta_attention_recall(const float *lse_window, const float *lse_full, int B,
                          size_t workspace_bytes, float *dev_recall,
                          float *dev_mean, void *hip_stream);
 
-/* Bytes of device scratch sta_forward needs for this problem (0 if none). */
+/* Bytes of device scratch with which sta_forward splits work below one query tile on the current device
+ * (0 when the kernels serving this shape do not split: D = 64, or P not a multiple of 128). */
 size_t sta_workspace_bytes(int B, int H, int D, const int grid[3],
                            const int tile[3]);
 

@@ -221,7 +221,12 @@ int sta_untile(const void *src, void *dst, int src_dt, int dst_dt, int B, int H,
     return permute_common(src, dst, src_dt, dst_dt, B, H, D, grid, tile, hip_stream, false);
 }
 
-size_t sta_workspace_bytes(int, int, int, const int *, const int *) { return 0; }
+size_t sta_workspace_bytes(int B, int H, int D, const int grid[3], const int tile[3])
+{
+    Shape s;
+    if (check_shape(B, H, D, grid, tile, &s) != STA_OK) return 0;
+    return sta::forward_split_workspace_bytes((int)s.P, D);
+}
 
 }  // extern "C"
 
@@ -229,7 +234,7 @@ namespace {
 
 int forward_common(const void *q_tiled, const void *k_tiled, const void *v_tiled, void *o_tiled, float *lse_tiled,
                    int B, int H, int D, const int grid[3], const int tile[3], const int *window_tiles, float scale,
-                   void *hip_stream)
+                   void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!q_tiled || !k_tiled || !v_tiled || !o_tiled) return STA_ERR_NULL;
     Shape s;
@@ -240,6 +245,13 @@ int forward_common(const void *q_tiled, const void *k_tiled, const void *v_tiled
     if (ranges_overlap(o_tiled, bytes, q_tiled, bytes) || ranges_overlap(o_tiled, bytes, k_tiled, bytes) ||
         ranges_overlap(o_tiled, bytes, v_tiled, bytes))
         return STA_ERR_ALIAS;
+    if (workspace != nullptr) {
+        if (workspace_bytes < sta::forward_split_workspace_bytes((int)s.P, D) || ((uintptr_t)workspace & 15) != 0)
+            return STA_ERR_WORKSPACE;
+        const void *tensors[4] = {q_tiled, k_tiled, v_tiled, o_tiled};
+        for (int i = 0; i < 4; ++i)
+            if (workspace_bytes != 0 && ranges_overlap(workspace, workspace_bytes, tensors[i], bytes)) return STA_ERR_ALIAS;
+    }
     if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
     sta::FwdParams p = make_fwd_params(s, H, scale * 1.4426950408889634f);
     if (lse_tiled) {
@@ -263,6 +275,7 @@ int forward_common(const void *q_tiled, const void *k_tiled, const void *v_tiled
         sta::HeadOrder order;
         fill_head_order(&order, window_tiles, hb, heads, s.n);
         hipError_t e = sta::launch_forward(q_tiled, k_tiled, v_tiled, o_tiled, B, D, p, win, order,
+                                           static_cast<float *>(workspace), workspace_bytes / sizeof(float),
                                            static_cast<hipStream_t>(hip_stream));
         if (e != hipSuccess) return STA_ERR_HIP;
     }
@@ -277,10 +290,8 @@ int sta_forward(const void *q_tiled, const void *k_tiled, const void *v_tiled, v
                 const int grid[3], const int tile[3], const int *window_tiles, float scale, void *workspace,
                 size_t workspace_bytes, void *hip_stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     return forward_common(q_tiled, k_tiled, v_tiled, o_tiled, nullptr, B, H, D, grid, tile, window_tiles, scale,
-                          hip_stream);
+                          workspace, workspace_bytes, hip_stream);
 }
 
 int sta_forward_lse(const void *q_tiled, const void *k_tiled, const void *v_tiled, void *o_tiled, float *lse_tiled,
@@ -289,7 +300,7 @@ int sta_forward_lse(const void *q_tiled, const void *k_tiled, const void *v_tile
 {
     if (!lse_tiled) return STA_ERR_NULL;
     return forward_common(q_tiled, k_tiled, v_tiled, o_tiled, lse_tiled, B, H, D, grid, tile, window_tiles, scale,
-                          hip_stream);
+                          nullptr, 0, hip_stream);
 }
 
 size_t sta_head_mse_workspace_bytes(int B, int H)
@@ -365,13 +376,14 @@ int sta_mask_search(const void *q_tiled, const void *k_tiled, const void *v_tile
     int win[3 * 4096];
     for (int h = 0; h < H; ++h)
         for (int a = 0; a < 3; ++a) win[3 * h + a] = s.n[a];                 // the original: full attention
-    if (int rc = forward_common(q_tiled, k_tiled, v_tiled, o_full, nullptr, B, H, D, grid, tile, win, scale, hip_stream))
+    if (int rc = forward_common(q_tiled, k_tiled, v_tiled, o_full, nullptr, B, H, D, grid, tile, win, scale, nullptr, 0,
+                                hip_stream))
         return rc;
     for (int p = 0; p < n_patterns; ++p) {
         for (int h = 0; h < H; ++h)
             for (int a = 0; a < 3; ++a) win[3 * h + a] = patterns[3 * p + a];
         if (int rc = forward_common(q_tiled, k_tiled, v_tiled, o_pattern, nullptr, B, H, D, grid, tile, win, scale,
-                                    hip_stream))
+                                    nullptr, 0, hip_stream))
             return rc;
         if (int rc = sta_head_mse(o_full, o_pattern, B, H, D, grid, workspace, workspace_bytes,
                                   dev_losses + (size_t)p * H, hip_stream))

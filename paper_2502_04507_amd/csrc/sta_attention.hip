@@ -245,6 +245,65 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
 }
 
 
+// Work items of the head-dim-128 kernels.  The hardware deals workgroup ids round-robin over the 8 XCDs (each with
+// its own L2) and, inside an XCD, starts them in increasing order.  Every (batch, head) slice is cut into 8
+// contiguous ranges of query blocks, one per XCD, so each XCD carries one eighth of every head whatever the
+// per-head windows are (load balance: with mixed per-head windows this halved the launch time), and its resident
+// workgroups are neighbouring query blocks of one head (shared K/V in L2).  Heads are visited in descending cost
+// order, so the tail of the launch is made of cheap items.  The price is that neighbouring ranges of a head fetch
+// the same border K/V tiles into two L2s: measured HBM-side reads rose by about 10 % against giving each XCD
+// whole heads.
+// Inside a head the query tiles are scheduled by pairs of tile rows (h), then w, then the row of the pair, then t
+// fastest, so that the ~32 tiles resident on an XCD at one time form a compact 3-D block, (all t) x (2 h) x
+// (about 3 w), and share key tiles along all three axes (measured: reads past L2 9.8 -> 6.4 GB per launch against
+// plain tile-id order, 12.81 -> 12.74 ms).
+struct FwdItem {
+    bool valid;
+    size_t bh;          // b * H + head
+    uint32_t qblock;    // index of the QB-query block inside the head
+    uint32_t h_local;   // head inside this launch
+};
+
+// id: position in the launch's list of work items (a workgroup id, or the item a split workgroup belongs to).
+template <int QB>
+__device__ __forceinline__ FwdItem fwd_item_of(uint32_t id, const sta::FwdParams &p, const sta::HeadOrder &order,
+                                               uint32_t n_bh)
+{
+    FwdItem it;
+    it.valid = false;
+    const uint32_t xcd = id & 7;
+    const uint32_t slot = id >> 3;
+    const uint32_t qblocks_per_head = p.N / QB;
+    const uint32_t seg_lo = (xcd * qblocks_per_head) >> 3;
+    const uint32_t seg_len = (((xcd + 1) * qblocks_per_head) >> 3) - seg_lo;
+    if (seg_len == 0) return it;
+    const uint32_t bh_rank = slot / seg_len;
+    if (bh_rank >= n_bh) return it;
+    const uint32_t pos = seg_lo + (slot - bh_rank * seg_len);
+    const uint32_t per_tile = p.P / QB;
+    const uint32_t sched = pos / per_tile, sub = pos - sched * per_tile;
+    const uint32_t pair_items = 2 * p.n_w * p.n_t;
+    const uint32_t hp = sched / pair_items;
+    uint32_t rem = sched - hp * pair_items;
+    const uint32_t rows = (p.n_h - 2 * hp) < 2 ? (p.n_h - 2 * hp) : 2;
+    const uint32_t w_ = rem / (rows * p.n_t);
+    rem -= w_ * rows * p.n_t;
+    const uint32_t hh = rem / p.n_t, t_ = rem - hh * p.n_t;
+    it.qblock = ((t_ * p.n_h + 2 * hp + hh) * p.n_w + w_) * per_tile + sub;
+    it.h_local = order.h[bh_rank / (n_bh / p.heads)];     // batch entries of one head are adjacent
+    it.bh = (size_t)(bh_rank % (n_bh / p.heads)) * p.H + p.head_base + it.h_local;
+    it.valid = true;
+    return it;
+}
+
+// Work splitting below one query block.  The last workgroups of a launch would run on a mostly idle chip (the
+// item count is rarely a multiple of the number of workgroups the chip holds).  The host therefore turns the
+// items from `split_first` on into `split_parts` workgroups each; part j walks the sub-blocks
+// [n*j/parts, n*(j+1)/parts) of the item's key walk and leaves its unnormalised accumulator, exponent offset and
+// row sum in the workspace, and sta_fwd_combine_kernel merges the parts of an item in a fixed order.
+// Workspace layout, per part (index = workgroup id - split_first): float O[QB][128], float m[QB], float l[QB].
+__device__ __forceinline__ size_t split_part_floats(int QB) { return (size_t)QB * 130; }
+
 // ---------------------------------------------------------------------------
 // Fast path: head dim 128.  NW waves x 32 queries per workgroup (one query block per wave; at least two waves
 // per SIMD on a CU, so one wave's softmax overlaps another's MFMAs), K/V sub-blocks of KB keys DMA'd
@@ -280,43 +339,18 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
 
     __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_BYTES];
 
-    // ---- work item.  The hardware deals workgroup ids round-robin over the 8 XCDs (each with its own L2) and,
-    // inside an XCD, starts them in increasing order.  Every (batch, head) slice is cut into 8 contiguous
-    // ranges of query blocks, one per XCD, so each XCD carries one eighth of every head whatever the per-head
-    // windows are (load balance: with mixed per-head windows this halved the launch time), and its resident
-    // workgroups are neighbouring query blocks of one head (shared K/V in L2).  Heads are visited in
-    // descending cost order, so the tail of the launch is made of cheap items.  The price is that
-    // neighbouring ranges of a head fetch the same border K/V tiles into two L2s: measured HBM-side reads
-    // rose by about 10 % against giving each XCD whole heads.
-    const uint32_t xcd = blockIdx.x & 7;
-    const uint32_t slot = blockIdx.x >> 3;
-    const uint32_t qblocks_per_head = p.N / QB;
-    const uint32_t seg_lo = (xcd * qblocks_per_head) >> 3;
-    const uint32_t seg_len = (((xcd + 1) * qblocks_per_head) >> 3) - seg_lo;
-    if (seg_len == 0) return;
-    const uint32_t bh_rank = slot / seg_len;
-    if (bh_rank >= n_bh) return;
-    // Position in the head's scheduling order -> query block.  The query tiles of a head are scheduled by pairs of
-    // tile rows (h), then w, then the row of the pair, then t fastest, so that the ~32 tiles resident on an XCD at
-    // one time form a compact 3-D block, (all t) x (2 h) x (about 3 w), and share key tiles along all three axes
-    // (measured: reads past L2 9.8 -> 6.4 GB per launch against plain tile-id order, 12.81 -> 12.74 ms).
-    uint32_t qblock;
-    {
-        const uint32_t pos = seg_lo + (slot - bh_rank * seg_len);
-        const uint32_t per_tile = p.P / QB;
-        const uint32_t sched = pos / per_tile, sub = pos - sched * per_tile;
-        const uint32_t pair_items = 2 * p.n_w * p.n_t;
-        const uint32_t hp = sched / pair_items;
-        uint32_t rem = sched - hp * pair_items;
-        const uint32_t rows = (p.n_h - 2 * hp) < 2 ? (p.n_h - 2 * hp) : 2;
-        const uint32_t w_ = rem / (rows * p.n_t);
-        rem -= w_ * rows * p.n_t;
-        const uint32_t hh = rem / p.n_t, t_ = rem - hh * p.n_t;
-        qblock = ((t_ * p.n_h + 2 * hp + hh) * p.n_w + w_) * per_tile + sub;
+    // ---- work item (see fwd_item_of), possibly one part of a split item
+    uint32_t item_id = blockIdx.x, part = 0;
+    const bool is_part = blockIdx.x >= p.split_first;
+    if (is_part) {
+        const uint32_t idx = blockIdx.x - p.split_first;
+        item_id = p.split_first + idx / p.split_parts;
+        part = idx - (item_id - p.split_first) * p.split_parts;
     }
-    const uint32_t h_local = order.h[bh_rank / (n_bh / p.heads)];     // batch entries of one head are adjacent
-    const uint32_t b = bh_rank % (n_bh / p.heads);
-    const size_t bh = (size_t)b * p.H + p.head_base + h_local;
+    const FwdItem item = fwd_item_of<QB>(item_id, p, order, n_bh);
+    if (!item.valid) return;
+    const uint32_t qblock = item.qblock, h_local = item.h_local;
+    const size_t bh = item.bh;
     const uint32_t q_tile = (qblock * QB) / p.P;
     const StaBox box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1],
                                            win.w[h_local][2], q_tile);
@@ -391,7 +425,9 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     float l_run = 0.f;            // this lane's share of the row sum
 
     const int sub_per_tile = p.P / KB;
-    const int n_iter = box.count() * sub_per_tile;
+    const int n_all = box.count() * sub_per_tile;           // sub-blocks of the whole item
+    const int iter_lo = is_part ? (int)((long long)n_all * part / p.split_parts) : 0;
+    const int n_iter = (is_part ? (int)((long long)n_all * (part + 1) / p.split_parts) : n_all) - iter_lo;
     // Order in which the key tiles of the box are visited.  Along each axis the box [lo, hi] holds e = hi-lo+1
     // consecutive tiles, hence exactly one tile of every residue class mod e; the walk takes them in the order
     // of that residue (k mod e = 0, 1, ..), i.e. it starts inside the box and wraps from hi to lo.  Query tiles
@@ -409,7 +445,22 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
         const size_t kt = ((size_t)it_t * p.n_h + it_h) * p.n_w + it_w;
         return kt * p.P * ROWB;
     };
-    size_t next_base = row_start();
+    // a part starts iter_lo sub-blocks into the walk: whole tiles first, then sub-blocks inside the tile
+    for (int skip = iter_lo / sub_per_tile; skip > 0; --skip) {
+        if (++it_w > box.w.hi) it_w = box.w.lo;
+        if (--left_w == 0) {
+            left_w = e_w;
+            it_w = start_w;
+            if (++it_h > box.h.hi) it_h = box.h.lo;
+            if (--left_h == 0) {
+                left_h = e_h;
+                it_h = start_h;
+                if (++it_t > box.t.hi) it_t = box.t.lo;
+            }
+        }
+    }
+    it_s = iter_lo % sub_per_tile;
+    size_t next_base = row_start() + (size_t)it_s * KB * ROWB;
     auto advance = [&]() {
         next_base += (size_t)KB * ROWB;
         if (++it_s == sub_per_tile) {
@@ -567,8 +618,27 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     }
 
     // ---- finalize -------------------------------------------------------------------
-    bf16_raw *oh = o + (bh * p.N + (size_t)qblock * QB + (size_t)wave * 32) * D;
     const float l_tot = half_swap_sum(l_run);
+    if (is_part) {
+        // unnormalised accumulator, offset and row sum of this part; the combine kernel does the rest
+        float *ws = p.split_ws + (size_t)(blockIdx.x - p.split_first) * split_part_floats(QB);
+        float *wo = ws + (size_t)(wave * 32 + lo) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                floatx4 ov;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) ov[t] = Oacc[db][4 * g + t];
+                *reinterpret_cast<floatx4 *>(wo + db * 32 + g * 8 + hb * 4) = ov;
+            }
+        if (hb == 0) {
+            ws[(size_t)QB * D + wave * 32 + lo] = m_run;
+            ws[(size_t)QB * D + QB + wave * 32 + lo] = l_tot;
+        }
+        return;
+    }
+    bf16_raw *oh = o + (bh * p.N + (size_t)qblock * QB + (size_t)wave * 32) * D;
     const float inv = 1.f / l_tot;
     // sum_j exp(s_j * scale) = 2^(m * scale_log2e) * l  =>  ln = m * scale_log2e * ln 2 + ln l
     if (p.lse != nullptr && hb == 0)
@@ -584,17 +654,117 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
         }
 }
 
-template <int NW, int KB, int STAGES, int MINB>
-hipError_t launch_fast_d128(const void *q, const void *k, const void *v, void *o, int B, const sta::FwdParams &p,
-                            const sta::WindowTable &win, const sta::HeadOrder &order, hipStream_t stream)
+// Merges the parts of every split item: one wave per query row, two channels per lane.  With m the largest of
+// the parts' offsets:  O = sum_j 2^((m_j - m) c) O_j / sum_j 2^((m_j - m) c) l_j, parts taken in ascending order.
+template <int QB>
+__global__ __launch_bounds__(256) void sta_fwd_combine_kernel(bf16_raw *__restrict__ o, sta::FwdParams p,
+                                                              sta::HeadOrder order, uint32_t n_bh)
 {
-    const uint32_t qblocks_per_head = p.N / (NW * 32);
+    constexpr int D = 128;
+    const uint32_t item_id = p.split_first + blockIdx.y;
+    const FwdItem item = fwd_item_of<QB>(item_id, p, order, n_bh);
+    if (!item.valid) return;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);       // query inside the block
+    const int lane = threadIdx.x & 63;
+    const float *ws = p.split_ws + (size_t)blockIdx.y * p.split_parts * split_part_floats(QB);
+    const float c = p.scale_log2e;
+    float m = -INFINITY;
+    for (uint32_t j = 0; j < p.split_parts; ++j) m = fmaxf(m, ws[j * split_part_floats(QB) + (size_t)QB * D + row]);
+    float l = 0.f, a0 = 0.f, a1 = 0.f;
+    for (uint32_t j = 0; j < p.split_parts; ++j) {
+        const float *part = ws + j * split_part_floats(QB);
+        const float w = exp2f((part[(size_t)QB * D + row] - m) * c);
+        l += w * part[(size_t)QB * D + QB + row];
+        const float2 x = *reinterpret_cast<const float2 *>(part + (size_t)row * D + 2 * lane);
+        a0 += w * x.x;
+        a1 += w * x.y;
+    }
+    const float inv = 1.f / l;
+    const size_t out_row = item.bh * p.N + (size_t)item.qblock * QB + row;
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 ov;
+    ov[0] = static_cast<__bf16>(a0 * inv);
+    ov[1] = static_cast<__bf16>(a1 * inv);
+    *reinterpret_cast<bf16x2 *>(o + out_row * D + 2 * lane) = ov;
+    if (p.lse != nullptr && lane == 0) p.lse[out_row] = m * c * 0.6931471805599453f + __logf(l);
+}
+
+// Host side of the work splitting: how many workgroups the chip holds at once.
+inline uint32_t resident_workgroups(int minb)
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return (uint32_t)cus * (uint32_t)minb;
+}
+
+template <int NW, int KB, int STAGES, int MINB>
+hipError_t launch_fast_d128(const void *q, const void *k, const void *v, void *o, int B, const sta::FwdParams &p_in,
+                            const sta::WindowTable &win, const sta::HeadOrder &order, float *split_ws,
+                            size_t split_ws_floats, hipStream_t stream)
+{
+    constexpr int QB = NW * 32;
+    sta::FwdParams p = p_in;
+    const uint32_t qblocks_per_head = p.N / QB;
     const uint32_t max_seg = (qblocks_per_head + 7) / 8;          // longest of the 8 per-XCD ranges
     const uint32_t n_bh = (uint32_t)B * p.heads;
-    dim3 grid(8 * max_seg * n_bh), block(NW * 64);
+    const uint32_t ids = 8 * max_seg * n_bh;                      // item ids; some of them name no item
+    p.split_first = ids;
+    p.split_parts = 1;
+    p.split_ws = nullptr;
+    uint32_t split_items = 0;
+    if (split_ws != nullptr) {
+        // Items beyond the last full round of workgroups are split so that their parts fill the chip once.
+        auto names_item = [&](uint32_t id) {
+            const uint32_t xcd = id & 7, slot = id >> 3;
+            const uint32_t seg_lo = (xcd * qblocks_per_head) >> 3;
+            const uint32_t seg_len = (((xcd + 1) * qblocks_per_head) >> 3) - seg_lo;
+            return seg_len != 0 && slot / seg_len < n_bh;
+        };
+        const uint32_t capacity = resident_workgroups(MINB);
+        const uint64_t items = (uint64_t)qblocks_per_head * n_bh;
+        const uint32_t tail = (uint32_t)(items % capacity);
+        if (tail != 0 && 2 * tail <= capacity) {
+            uint32_t parts = capacity / tail;
+            // a part should keep at least four sub-blocks of the cheapest item of the launch
+            uint32_t min_tiles = 0xffffffffu;
+            for (uint32_t h = 0; h < p.heads; ++h) {
+                uint32_t tiles = 1;
+                const uint32_t n[3] = {p.n_t, p.n_h, p.n_w};
+                for (int a = 0; a < 3; ++a) {
+                    const uint32_t kept = 2 * (win.w[h][a] / 2) + 1;
+                    tiles *= kept < n[a] ? kept : n[a];
+                }
+                min_tiles = tiles < min_tiles ? tiles : min_tiles;
+            }
+            const uint32_t min_iters = min_tiles * (p.P / KB);
+            while (parts > 1 && min_iters / parts < 4) --parts;
+            uint32_t first = ids, found = 0;
+            while (first > 0 && found < tail) {
+                --first;
+                if (names_item(first)) ++found;
+            }
+            const size_t need = (size_t)(ids - first) * parts * ((size_t)QB * 130);
+            if (parts > 1 && found == tail && need <= split_ws_floats) {
+                p.split_first = first;
+                p.split_parts = parts;
+                p.split_ws = split_ws;
+                split_items = ids - first;
+            }
+        }
+    }
+    dim3 grid(p.split_first + split_items * p.split_parts), block(NW * 64);
     sta_fwd_d128_kernel<NW, KB, STAGES, MINB><<<grid, block, 0, stream>>>(
         static_cast<const bf16_raw *>(q), static_cast<const bf16_raw *>(k), static_cast<const bf16_raw *>(v),
         static_cast<bf16_raw *>(o), p, win, order, n_bh);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || split_items == 0) return e;
+    sta_fwd_combine_kernel<QB><<<dim3(QB / 4, split_items), dim3(256), 0, stream>>>(static_cast<bf16_raw *>(o), p, order, n_bh);
     return hipGetLastError();
 }
 
@@ -649,8 +819,18 @@ bool g_force_generic = false;
 
 bool forward_supported(int P, int D) { return (D == 64 || D == 128) && P > 0 && P % 32 == 0; }
 
+size_t forward_split_workspace_bytes(int P, int D)
+{
+    if (D != 128 || P % 128 != 0 || g_force_generic) return 0;
+    // About one resident set of workgroups leaves partial results, QB queries x (128 + 2) floats each; twice
+    // that, because ids that name no item (ranges of unequal length) also take a slot.
+    if (P % 384 == 0) return (size_t)2 * resident_workgroups(1) * 384 * 130 * sizeof(float);
+    return (size_t)2 * resident_workgroups(2) * 128 * 130 * sizeof(float);
+}
+
 hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, int B, int D, const FwdParams &p,
-                          const WindowTable &win, const HeadOrder &order, hipStream_t stream)
+                          const WindowTable &win, const HeadOrder &order, float *split_ws, size_t split_ws_floats,
+                          hipStream_t stream)
 {
     if (!forward_supported((int)p.P, D)) return hipErrorInvalidValue;
     if (D == 64) return launch_d<64>(q, k, v, o, B, p, win, stream);
@@ -658,8 +838,10 @@ hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, 
     // fetched from L2 then serves 384 queries instead of 128.  Measured at the 115,200-token layer, window
     // 3x3x3: 12.8-13.1 ms against 13.6-13.7 ms for the 4-wave shape in the same session; 2 LDS stages were
     // faster than 3 (13.15 ms) or 4 (13.3 ms).
-    if (p.P % 384 == 0 && !sta::g_force_generic) return launch_fast_d128<12, 32, 2, 1>(q, k, v, o, B, p, win, order, stream);
-    if (p.P % 128 == 0 && !sta::g_force_generic) return launch_fast_d128<4, 64, 2, 2>(q, k, v, o, B, p, win, order, stream);
+    if (p.P % 384 == 0 && !sta::g_force_generic)
+        return launch_fast_d128<12, 32, 2, 1>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
+    if (p.P % 128 == 0 && !sta::g_force_generic)
+        return launch_fast_d128<4, 64, 2, 2>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
     return launch_d<128>(q, k, v, o, B, p, win, stream);
 }
 

@@ -43,12 +43,19 @@ struct FwdParams {
     uint32_t heads;        // heads in this launch
     float scale_log2e;     // softmax scale * log2(e)
     float *lse = nullptr;  // optional output [B,H,N] (tiled order): ln of each row's softmax denominator; may be null
+    // work splitting below one query block (filled in by the launcher): item ids from split_first on are run
+    // by split_parts workgroups each, which leave partial results in split_ws
+    uint32_t split_first = 0xffffffffu;
+    uint32_t split_parts = 1;
+    float *split_ws = nullptr;
 };
 
 // Returns hipErrorInvalidValue if no kernel instance exists for (P, D).
+// split_ws: optional device scratch for work splitting (null: every item is run by one workgroup).
 hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, int B, int D,
-                          const FwdParams &p, const WindowTable &win, const HeadOrder &order,
-                          hipStream_t stream);
+                          const FwdParams &p, const WindowTable &win, const HeadOrder &order, float *split_ws,
+                          size_t split_ws_floats, hipStream_t stream);
+size_t forward_split_workspace_bytes(int P, int D);    // upper bound of what the splitting ever uses
 bool forward_supported(int P, int D);
 extern bool g_force_generic;   // debugging aid: route every shape through the generic kernel
 

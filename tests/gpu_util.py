@@ -18,7 +18,13 @@ REL_FRO_TOL = 1e-2
 COSINE_MIN = 0.9999
 
 
-def gpu_chain(w, q, k, v, scale=0.0, device="cuda:0"):
+def forward_workspace(w, device="cuda:0"):
+    """Device scratch of the size sta_workspace_bytes asks for (lets sta_forward split work below one query tile)."""
+    nbytes = sta.sta_workspace_bytes(w.B, w.H, w.D, w.grid, w.tile)
+    return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+
+
+def gpu_chain(w, q, k, v, scale=0.0, device="cuda:0", workspace=True):
     """tile_permute(Q,K,V) -> sta_forward -> untile, all in the HIP library.
     q, k, v: host tensors [B,H,N,D] in raster order (bf16 or f32).  Returns raster O (bf16, host)."""
     qd, kd, vd = (x.to(device) for x in (q, k, v))
@@ -28,7 +34,8 @@ def gpu_chain(w, q, k, v, scale=0.0, device="cuda:0"):
     sta.sta_tile_permute(kd, kt, w.grid, w.tile)
     sta.sta_tile_permute(vd, vt, w.grid, w.tile)
     ot.fill_(float("nan"))
-    sta.sta_forward(qt, kt, vt, ot, w.grid, w.tile, w.window_tiles, scale=scale)
+    ws = forward_workspace(w, device) if workspace else None
+    sta.sta_forward(qt, kt, vt, ot, w.grid, w.tile, w.window_tiles, scale=scale, workspace=ws)
     o.fill_(float("nan"))
     sta.sta_untile(ot, o, w.grid, w.tile)
     torch.cuda.synchronize()
@@ -83,3 +90,23 @@ def border_and_interior_tiles(w):
     picks = {rm(0, 0, 0), rm(nt - 1, nh - 1, nw - 1), rm(nt // 2, 0, nw // 2), rm(nt // 2, nh // 2, nw // 2),
              rm(0, nh - 1, nw // 2)}
     return sorted(picks)
+
+
+def strata_tiles(w):
+    """Query tiles by stratum of the tile grid: all corners, one tile per edge direction and per face direction
+    (where the grid has them), and up to four interior tiles.  Row-major tile ids, no duplicates, corners first."""
+    nt, nh, nw = w.tile_grid
+    rm = lambda a, b, c: (a * nh + b) * nw + c
+    ends = lambda n: sorted({0, n - 1})
+    mid = lambda n: n // 2
+    picks = [rm(a, b, c) for a in ends(nt) for b in ends(nh) for c in ends(nw)]                      # corners
+    picks += [rm(mid(nt), 0, 0), rm(0, mid(nh), nw - 1), rm(nt - 1, nh - 1, mid(nw))]                 # edges
+    picks += [rm(0, mid(nh), mid(nw)), rm(mid(nt), nh - 1, mid(nw)), rm(mid(nt), mid(nh), 0)]         # faces
+    inner = [(a, b, c) for a in range(1, max(nt - 1, 1)) for b in range(1, max(nh - 1, 1)) for c in range(1, max(nw - 1, 1))]
+    step = max(len(inner) // 4, 1)
+    picks += [rm(*x) for x in inner[::step][:4]]                                                     # interior
+    out = []
+    for t in picks:
+        if t not in out:
+            out.append(t)
+    return out

@@ -105,7 +105,16 @@ def test_error_returns_before_any_launch():
     lo, hi = I3(), I3()
     assert lib.sta_key_tile_box(I3(2, 2, 2), I3(1, 1, 1), I3(0, 0, 2), lo, hi) == 2
     assert lib.sta_key_tile_box(I3(2, 2, 2), I3(1, 0, 1), I3(0, 0, 1), lo, hi) == 3
-    assert sta.sta_workspace_bytes(1, 24, 128, (30, 48, 80), (6, 8, 8)) == 0
+    # workspace: a positive size for the shapes whose kernels split work, zero otherwise; too small is an error
+    need = sta.sta_workspace_bytes(1, 24, 128, (30, 48, 80), (6, 8, 8))
+    assert need > 0 and need % 16 == 0
+    assert sta.sta_workspace_bytes(1, 8, 64, (1, 64, 64), (1, 8, 8)) == 0
+    assert sta.sta_workspace_bytes(1, 1, 128, (4, 4, 6), (2, 2, 8)) == 0          # P = 32
+    win24 = (ctypes.c_int * 72)(*([3] * 72))
+    assert lib.sta_forward(fake, fake, fake, fake2, 1, 24, 128, I3(30, 48, 80), I3(6, 8, 8), win24, 0.0,
+                           ctypes.c_void_p(0x40000000), need - 16, None) == 6
+    assert lib.sta_forward(fake, fake, fake, fake2, 1, 24, 128, I3(30, 48, 80), I3(6, 8, 8), win24, 0.0,
+                           ctypes.c_void_p(0x40000008), need, None) == 6
 
 
 @pytest.mark.parametrize("grid,tile,win", [

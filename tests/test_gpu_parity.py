@@ -210,14 +210,42 @@ def test_forward_is_bit_reproducible(tile, grid):
     sta.sta_tile_permute(qd, qt, w.grid, w.tile)
     sta.sta_tile_permute(kd, kt, w.grid, w.tile)
     sta.sta_tile_permute(vd, vt, w.grid, w.tile)
-    outs = []
-    for _ in range(4):
-        o = torch.full_like(qt, float("nan"))
-        sta.sta_forward(qt, kt, vt, o, w.grid, w.tile, w.window_tiles)
-        outs.append(o)
-    torch.cuda.synchronize()
-    for o in outs[1:]:
-        assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16))
+    ws = gu.forward_workspace(w, DEV)
+    for workspace in (None, ws):          # without and with work splitting below one query tile
+        outs = []
+        for _ in range(4):
+            o = torch.full_like(qt, float("nan"))
+            sta.sta_forward(qt, kt, vt, o, w.grid, w.tile, w.window_tiles, workspace=workspace)
+            outs.append(o)
+        torch.cuda.synchronize()
+        for o in outs[1:]:
+            assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16))
+
+
+@pytest.mark.parametrize("tile,grid,windows", [
+    ((6, 8, 8), (12, 24, 32), [(1, 3, 3), (3, 1, 2), (2, 3, 4)]),      # 12-wave kernel, 24 items per head
+    ((2, 8, 8), (4, 24, 32), [(2, 3, 4), (3, 3, 3), (2, 2, 2)]),       # 4-wave kernel; >= 8 kept tiles per head
+])
+def test_split_items_match_whole_items_and_the_oracle(tile, grid, windows):
+    """With a workspace the last (here: all) work items are cut along the keys into parts whose partial results
+    a second kernel merges; the result must agree with the one-workgroup-per-item run to rounding and with the
+    oracle to the usual tolerance.  A workspace that is too small is an error, not a silent fallback."""
+    w = syn.custom("split", 1, len(windows), 128, grid, tile, windows, "bf16", seed=4242)
+    assert sta.sta_workspace_bytes(w.B, w.H, w.D, w.grid, w.tile) > 0
+    q, k, v = syn.make_qkv(w)
+    whole = gu.gpu_chain(w, q, k, v, workspace=False).float().numpy()
+    split = gu.gpu_chain(w, q, k, v, workspace=True).float().numpy()
+    assert np.isfinite(split).all()
+    assert np.abs(split - whole).max() <= 2.0 ** -7 * np.abs(whole).max()      # both round the same value to bf16
+    assert (split != whole).any(), "the split path was not taken"
+    for h in range(w.H):
+        ref = gu.oracle_rows(w, q, k, v, 0, h, None)
+        gu.assert_parity(split[0, h], ref, "split h%d" % h)
+    qd = q.to(DEV)
+    small = torch.empty(64, dtype=torch.uint8, device=DEV)
+    with pytest.raises(sta.StaError) as e:
+        sta.sta_forward(qd, qd, qd, torch.empty_like(qd), w.grid, w.tile, w.window_tiles, workspace=small)
+    assert e.value.status == 6
 
 
 def test_attention_explicit_scale():
@@ -239,13 +267,20 @@ def test_full_window_equals_dense_attention_on_gpu():
         gu.assert_parity(out[0, h].numpy(), ref.numpy(), "dense h%d" % h)
 
 
-def test_kept_set_read_from_gpu_output():
+@pytest.mark.parametrize("D,grid,tile,workspace", [
+    (64, (12, 24, 32), (6, 8, 8), False),          # generic kernel, ascending walk
+    (128, (12, 24, 32), (6, 8, 8), False),         # 12-wave kernel: residue-order walk of the box
+    (128, (12, 24, 32), (6, 8, 8), True),          # ... with items split along the keys
+    (128, (4, 24, 32), (2, 8, 8), False),          # 4-wave kernel
+    (128, (4, 24, 32), (2, 8, 8), True),
+    (128, (6, 40, 48), (6, 8, 8), False),          # 1x5x6 = 30 tiles: boxes that wrap along two axes
+])
+def test_kept_set_read_from_gpu_output(D, grid, tile, workspace):
     """Q = 0 and V = one-hot(tile id): O[i, tau] = [tau kept] / kept(q tile), which reads the
-    kept set and its size straight out of the kernel's output."""
-    grid, tile = (12, 16, 16), (6, 8, 8)          # 2x2x2 = 8 tiles... widened below
-    grid, tile = (12, 24, 32), (6, 8, 8)          # 2x3x4 = 24 tiles, P = 384
-    windows = [(1, 3, 3), (3, 1, 2), (1, 1, 1), (2, 3, 4)]
-    w = syn.custom("onehot", 1, len(windows), 64, grid, tile, windows, "bf16", seed=11)
+    kept set and its size straight out of the kernel's output, for every kernel that walks the box."""
+    windows = [(1, 3, 3), (3, 1, 2), (1, 1, 1), (2, 3, 4), (1, 5, 3), (3, 9, 9)]
+    w = syn.custom("onehot", 1, len(windows), D, grid, tile, windows, "bf16", seed=11)
+    assert w.n_tiles <= D
     n = w.n_tiles
     order = orc.tile_order(grid, tile)
     tile_of_raster = np.empty(w.N, dtype=np.int64)
@@ -254,7 +289,7 @@ def test_kept_set_read_from_gpu_output():
     _, k, _ = syn.make_qkv(w)
     v = torch.zeros((1, w.H, w.N, w.D), dtype=torch.bfloat16)
     v[0, :, torch.arange(w.N), torch.from_numpy(tile_of_raster)] = 1.0
-    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    out = gu.gpu_chain(w, q, k, v, workspace=workspace).float().numpy()
     for h, wt in enumerate(windows):
         counts, lists = orc.key_tiles(grid, tile, orc.window_tiles_to_tokens(wt, tile))
         for qt in range(n):
@@ -291,32 +326,57 @@ def test_attention_parity_c3_sampled():
         gu.assert_parity(out[0, h, idx], ref, "C3 h%d" % h)
 
 
-def _sampled_full_size(name, n_random, heads_with_full_tile, heads=None):
+def _sampled_full_size(name, n_random, heads_with_full_tile, heads=None, rows_per_stratum=16, strata_per_head=3):
+    """Full-size run in the launch configuration the benchmark times (workspace given, so the last round of work
+    items is split).  Every head is checked on n_random random rows plus rows_per_stratum rows of each of
+    strata_per_head query tiles taken in turn from the strata of the tile grid: the 8 corners, one tile per
+    edge and face class, interior tiles."""
     w = syn.workload(name)
     q, k, v = syn.make_qkv(w)
     out = gu.gpu_chain(w, q, k, v).float().numpy()
     assert np.isfinite(out).all()
-    tiles = gu.border_and_interior_tiles(w)
-    stats = []
-    for h in (heads if heads is not None else range(w.H)):
-        full = [tiles[h % len(tiles)]] if h in heads_with_full_tile else []
-        idx = gu.stratified_query_sample(w, n_random, full, seed=200 + h)
+    strata = gu.strata_tiles(w)
+    order = orc.tile_order(w.grid, w.tile)
+    stats, used = [], set()
+    head_list = list(heads if heads is not None else range(w.H))
+    for i, h in enumerate(head_list):
+        rng = np.random.default_rng(300 + h)
+        idx = [rng.integers(0, w.N, size=n_random)]
+        for j in range(strata_per_head):
+            t = strata[(i * strata_per_head + j) % len(strata)]
+            used.add(t)
+            rows = order[t * w.P:(t + 1) * w.P]
+            idx.append(rows if h in heads_with_full_tile and j == 0 else rng.choice(rows, size=rows_per_stratum, replace=False))
+        idx = np.unique(np.concatenate(idx)).astype(np.int64)
         ref = gu.oracle_rows(w, q, k, v, 0, h, idx)
         stats.append(gu.assert_parity(out[0, h, idx], ref, "%s h%d" % (name, h)))
+    assert len(used) == min(len(strata), len(head_list) * strata_per_head)
     return stats
 
 
 def test_attention_parity_c4_sampled():
-    """HunyuanVideo-shaped layer, 3x3x3 window, in the launch configuration the benchmark times."""
-    _sampled_full_size("C4", n_random=32, heads_with_full_tile={0, 13})
+    """HunyuanVideo-shaped layer, 3x3x3 window: 24 heads x 3 strata tiles cover all 8 corners, the edge and face
+    classes and the interior tiles of the 5x6x10 tile grid."""
+    _sampled_full_size("C4", n_random=16, heads_with_full_tile={0, 13})
 
 
 def test_attention_parity_c5_mixed_windows_sampled():
-    _sampled_full_size("C5", n_random=16, heads_with_full_tile=set())
+    _sampled_full_size("C5", n_random=8, heads_with_full_tile=set(), rows_per_stratum=8)
 
 
 def test_attention_parity_c4_dense_sampled():
-    _sampled_full_size("C4dense", n_random=8, heads_with_full_tile=set(), heads=[0, 7, 23])
+    _sampled_full_size("C4dense", n_random=16, heads_with_full_tile=set(), heads=[0, 7, 23], rows_per_stratum=16)
+
+
+def test_many_batch_entries_take_the_head_chunk_limit():
+    """B = 300: the number of heads per launch is cut to 65535 / B, the limit of the generic kernel's grid."""
+    w = syn.custom("manybatch", 300, 2, 64, (1, 8, 16), (1, 8, 8), [(1, 1, 1), (1, 1, 3)], "bf16", seed=77)
+    q, k, v = syn.make_qkv(w)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    for b in (0, 151, 299):
+        for h in range(w.H):
+            ref = gu.oracle_rows(w, q, k, v, b, h, None)
+            gu.assert_parity(out[b, h], ref, "manybatch b%d h%d" % (b, h))
 
 
 # --------------------------------------------------------------------------
