@@ -238,18 +238,6 @@ int sta_block_census(int mask_kind, const int grid[3], const int tile[3],
                      int64_t *mixed_per_q, int64_t totals[3]);
 
 /*
- * Measurement aid for the roofline: runs nothing but the matrix instruction the attention kernels use
- * (v_mfma_f32_32x32x16_bf16, 16 per wave per iteration, with the dependency structure of one attention
- * sub-block) on `workgroups` workgroups of 4 waves, so that the caller can time what the matrix pipes of
- * the chip deliver for operands with given bit patterns (the clock the chip holds depends on them).
- * dev_operands: device, 16 KB of bf16 values chosen by the caller; dev_sink: device, float32
- * [workgroups * 256], written.  Work = workgroups * 4 * iters * 16 * 32768 flop.  iters >= 1,
- * 1 <= workgroups <= 65536.
- */
-int sta_probe_mfma(const void *dev_operands, int iters, int workgroups, float *dev_sink,
-                   void *hip_stream);
-
-/*
  * Window in tokens (the paper's notation, e.g. (18,24,24)) -> window in
  * tiles.  STA_ERR_WINDOW unless every entry is a positive multiple of the
  * tile size (Sec. 3.1 assumes W is an integer multiple of T).

@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = (
     "sta_tile_permute", "sta_untile", "sta_forward", "sta_forward_lse", "sta_workspace_bytes", "sta_key_tile_box",
     "sta_dump_key_tiles", "sta_window_tokens_to_tiles", "sta_kept_flops", "sta_strerror", "sta_version",
     "sta_head_mse_workspace_bytes", "sta_head_mse", "sta_mask_search", "sta_attention_recall", "sta_block_census",
-    "sta_backward_workspace_bytes", "sta_backward", "sta_query_tile_box", "sta_probe_mfma", "sta_head_mse_static",
+    "sta_backward_workspace_bytes", "sta_backward", "sta_query_tile_box", "sta_head_mse_static",
 )
 
 
@@ -82,8 +82,6 @@ def load_library():
     lib.sta_backward.restype = ci
     lib.sta_query_tile_box.argtypes = [_I3, _I3, _I3, _I3, _I3]
     lib.sta_query_tile_box.restype = ci
-    lib.sta_probe_mfma.argtypes = [vp, ci, ci, vp, vp]
-    lib.sta_probe_mfma.restype = ci
     lib.sta_block_census.argtypes = [ci, _I3, _I3, _I3, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.sta_block_census.restype = ci
     lib.sta_strerror.argtypes = [ci]
@@ -228,18 +226,6 @@ def sta_backward(q_tiled, k_tiled, v_tiled, o_tiled, d_o_tiled, lse_tiled, d_q_t
                             _windows(window_tiles, H), float(scale), _dev(workspace, "workspace"),
                             workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
     return d_q_tiled, d_k_tiled, d_v_tiled
-
-
-def sta_probe_mfma(operands, iters, workgroups, sink, stream=None):
-    """Matrix-instruction-only kernel for the roofline measurement.  operands: bf16 tensor of at least 8192
-    elements; sink: float32 tensor of at least workgroups*256 elements.  Returns the flop count of the launch."""
-    if operands.dtype != torch.bfloat16 or operands.numel() < 8192:
-        raise ValueError("operands must hold at least 8192 bf16 values")
-    if sink.dtype != torch.float32 or sink.numel() < workgroups * 256:
-        raise ValueError("sink must hold workgroups*256 float32 values")
-    _check(load_library().sta_probe_mfma(_dev(operands, "operands"), int(iters), int(workgroups), _dev(sink, "sink"),
-                                         _stream_ptr(stream)))
-    return float(workgroups) * 4 * int(iters) * 16 * 32768
 
 
 def sta_query_tile_box(grid_tiles, window_tiles, k_tile):

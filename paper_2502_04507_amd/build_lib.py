@@ -1,4 +1,5 @@
-"""Build libsta.so (the C-ABI HIP library) for gfx950 with hipcc, in-tree."""
+"""Build libsta.so (the C-ABI HIP library) and libsta_mfma_probe.so (a matrix-instruction-only kernel that the
+benchmark alone loads) for gfx950 with hipcc, in-tree."""
 import os
 import subprocess
 import sys
@@ -9,6 +10,8 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libsta.so")
 BUILD_DIR = os.path.join(HERE, "_build")
 SOURCES = ["sta_api.hip", "sta_permute.hip", "sta_attention.hip", "sta_reduce.hip", "sta_backward.hip"]
+PROBE_SOURCE = "bench_mfma_probe.hip"
+PROBE_OUT = os.path.join(HERE, "libsta_mfma_probe.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -37,14 +40,15 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = False) -> str:
     os.makedirs(BUILD_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT] + objs
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
-    if verbose:
-        print(OUT)
+    with ThreadPoolExecutor(max_workers=len(SOURCES) + 1) as ex:
+        objs = list(ex.map(_compile, SOURCES + [PROBE_SOURCE]))
+    for out, members in ((OUT, objs[:-1]), (PROBE_OUT, objs[-1:])):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + members
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+        if verbose:
+            print(out)
     return OUT
 
 

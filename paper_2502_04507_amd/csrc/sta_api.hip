@@ -545,14 +545,6 @@ int sta_block_census(int mask_kind, const int grid[3], const int tile[3], const 
     return STA_OK;
 }
 
-int sta_probe_mfma(const void *dev_operands, int iters, int workgroups, float *dev_sink, void *hip_stream)
-{
-    if (!dev_operands || !dev_sink) return STA_ERR_NULL;
-    if (iters < 1 || workgroups < 1 || workgroups > 65536) return STA_ERR_SHAPE;
-    hipError_t e = sta::launch_probe_mfma(dev_operands, iters, workgroups, dev_sink, static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? STA_OK : STA_ERR_HIP;
-}
-
 int sta_window_tokens_to_tiles(const int window_tokens[3], const int tile[3], int out_tiles[3])
 {
     if (!window_tokens || !tile || !out_tiles) return STA_ERR_NULL;

@@ -79,7 +79,6 @@ hipError_t launch_recall(const float *lse_window, const float *lse_full, int BH,
                          double *partial, float *mean_bh, hipStream_t stream);
 
 // 16 MFMAs per wave per iteration, 4 waves per workgroup; operands: 16 KB of bf16; sink: workgroups*256 floats.
-hipError_t launch_probe_mfma(const void *operands, int iters, int workgroups, float *sink, hipStream_t stream);
 
 hipError_t launch_dump_key_tiles(const FwdParams &p, const WindowTable &win, int32_t *counts,
                                  int32_t *lists, hipStream_t stream);

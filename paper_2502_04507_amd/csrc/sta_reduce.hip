@@ -124,51 +124,9 @@ __global__ void sta_recall_finish_kernel(const double *__restrict__ partial, int
     mean_bh[i] = (float)(s * inv_n);
 }
 
-// Measurement aid: what the matrix pipes deliver on THIS chip for the instruction the attention kernels use.
-// Each wave runs `iters` rounds of 16 v_mfma_f32_32x32x16_bf16 (8 chained into one accumulator like a QK^T
-// block, 8 into four accumulators like a PV block) on operands taken from `operands` (so their bit patterns, and
-// with them the power drawn and the clock the chip settles at, are the caller's choice) and nothing else.
-typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
-typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
-__global__ __launch_bounds__(256, 2) void sta_probe_mfma_kernel(const probe_bf16x8 *__restrict__ operands, int iters,
-                                                                float *__restrict__ sink)
-{
-    probe_bf16x8 a[8], b[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        a[i] = operands[(threadIdx.x & 63) + 64 * i];
-        b[i] = operands[(threadIdx.x & 63) + 64 * (8 + i)];
-    }
-    probe_floatx16 s, o[4];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        s[r] = 0.f;
-#pragma unroll
-        for (int d = 0; d < 4; ++d) o[d][r] = 0.f;
-    }
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[i], s, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[i], a[i], o[i & 3], 0, 0, 0);
-        asm volatile("" : "+v"(a[0]));      // nothing is loop-invariant
-    }
-    float acc = s[0] + s[7];
-#pragma unroll
-    for (int d = 0; d < 4; ++d) acc += o[d][3];
-    sink[blockIdx.x * blockDim.x + threadIdx.x] = acc;
-}
-
 }  // namespace
 
 namespace sta {
-
-hipError_t launch_probe_mfma(const void *operands, int iters, int workgroups, float *sink, hipStream_t stream)
-{
-    sta_probe_mfma_kernel<<<dim3(workgroups), dim3(256), 0, stream>>>(static_cast<const probe_bf16x8 *>(operands), iters,
-                                                                      sink);
-    return hipGetLastError();
-}
 
 hipError_t launch_head_mse(const void *a, const void *b, int B, int H, size_t elems_per_head, double *partial,
                            float *mse_per_head, hipStream_t stream)

@@ -127,3 +127,23 @@ def make_qkv_device(w: Workload, device="cuda:0"):
     shape = (w.B, w.H, w.N, w.D)
     dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     return tuple(torch.randn(shape, generator=g, dtype=torch.float32, device=device).to(dt) for _ in range(3))
+
+
+def strata_tiles(w):
+    """Query tiles by stratum of the tile grid: all corners, one tile per edge direction and per face direction
+    (where the grid has them), and up to four interior tiles.  Row-major tile ids, no duplicates, corners first."""
+    nt, nh, nw = w.tile_grid
+    rm = lambda a, b, c: (a * nh + b) * nw + c
+    ends = lambda n: sorted({0, n - 1})
+    mid = lambda n: n // 2
+    picks = [rm(a, b, c) for a in ends(nt) for b in ends(nh) for c in ends(nw)]                      # corners
+    picks += [rm(mid(nt), 0, 0), rm(0, mid(nh), nw - 1), rm(nt - 1, nh - 1, mid(nw))]                 # edges
+    picks += [rm(0, mid(nh), mid(nw)), rm(mid(nt), nh - 1, mid(nw)), rm(mid(nt), mid(nh), 0)]         # faces
+    inner = [(a, b, c) for a in range(1, max(nt - 1, 1)) for b in range(1, max(nh - 1, 1)) for c in range(1, max(nw - 1, 1))]
+    step = max(len(inner) // 4, 1)
+    picks += [rm(*x) for x in inner[::step][:4]]                                                     # interior
+    out = []
+    for t in picks:
+        if t not in out:
+            out.append(t)
+    return out

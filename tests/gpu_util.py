@@ -4,6 +4,7 @@ import numpy as np
 import torch
 
 import paper_2502_04507_amd as sta
+import synth_inputs as syn
 from oracle import sta_oracle as orc
 
 # Pass/fail contract for the bf16 attention output against the fp64 oracle.
@@ -92,21 +93,4 @@ def border_and_interior_tiles(w):
     return sorted(picks)
 
 
-def strata_tiles(w):
-    """Query tiles by stratum of the tile grid: all corners, one tile per edge direction and per face direction
-    (where the grid has them), and up to four interior tiles.  Row-major tile ids, no duplicates, corners first."""
-    nt, nh, nw = w.tile_grid
-    rm = lambda a, b, c: (a * nh + b) * nw + c
-    ends = lambda n: sorted({0, n - 1})
-    mid = lambda n: n // 2
-    picks = [rm(a, b, c) for a in ends(nt) for b in ends(nh) for c in ends(nw)]                      # corners
-    picks += [rm(mid(nt), 0, 0), rm(0, mid(nh), nw - 1), rm(nt - 1, nh - 1, mid(nw))]                 # edges
-    picks += [rm(0, mid(nh), mid(nw)), rm(mid(nt), nh - 1, mid(nw)), rm(mid(nt), mid(nh), 0)]         # faces
-    inner = [(a, b, c) for a in range(1, max(nt - 1, 1)) for b in range(1, max(nh - 1, 1)) for c in range(1, max(nw - 1, 1))]
-    step = max(len(inner) // 4, 1)
-    picks += [rm(*x) for x in inner[::step][:4]]                                                     # interior
-    out = []
-    for t in picks:
-        if t not in out:
-            out.append(t)
-    return out
+strata_tiles = syn.strata_tiles
