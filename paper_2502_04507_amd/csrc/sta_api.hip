@@ -476,7 +476,7 @@ int sta_backward(const void *q_tiled, const void *k_tiled, const void *v_tiled, 
         p.heads = heads;
         hipError_t e = sta::launch_backward(q_tiled, k_tiled, v_tiled, o_tiled, d_o_tiled, lse_tiled,
                                             static_cast<float *>(workspace), hb == 0, d_q_tiled, d_k_tiled, d_v_tiled, B,
-                                            p, win, static_cast<hipStream_t>(hip_stream));
+                                            D, p, win, static_cast<hipStream_t>(hip_stream));
         if (e != hipSuccess) return STA_ERR_HIP;
     }
     return STA_OK;

@@ -27,7 +27,8 @@
 // rows swz takes 16 different values (row reads of one chunk column hit 16 different bank groups), and over the
 // 4 rows a transposing read touches its upper two bits differ (the four 64-byte channel groups go to four
 // different quarters of the row).
-// Head dimension 128; tokens per tile a multiple of 128.
+// These kernels: head dimension 128, tokens per tile a multiple of 128.  Other shapes (head dimension 64, tiles
+// that are multiples of 32 tokens) go through the simple kernels further down.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -513,19 +514,285 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
     else store_columns(d_k + my_row * kD, lane, acc, c * kLn2);
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// General shapes: head dimension 64 or 128, any tile size that is a multiple of 32 tokens.  Same mathematics and
+// the same MFMA formulation (one lane owns one column, P or dS goes from the accumulators into the B operand),
+// kept simple: one wave per workgroup and 32 columns, staged operands copied through registers into a
+// row-major LDS block without swizzle (the row reads take bank conflicts), one sub-block at a time.  The fast
+// kernels above take over where they apply.
+// ---------------------------------------------------------------------------------------------------------
+template <int D>
+struct GenericOps {
+    static constexpr int RowB = 2 * D;             // bytes per token row
+    static constexpr int SubB = kSub * RowB;       // one staged operand
+    static constexpr int KS = D / 16;              // k-steps of a product over the channels
+    static constexpr int DB = D / 32;              // 32-channel blocks of an accumulator over the channels
+
+    // One wave copies a 32-row sub-block (contiguous in global memory) to LDS, 16 bytes per lane and step.
+    static __device__ __forceinline__ void copy_in(char *dst, const char *src, int lane)
+    {
+#pragma unroll
+        for (int i = 0; i < SubB / 1024; ++i)
+            *reinterpret_cast<uint4 *>(dst + i * 1024 + lane * 16) = *reinterpret_cast<const uint4 *>(src + i * 1024 + lane * 16);
+    }
+    // acc(32 x 32) = A B, A = staged sub-block read by rows (k = channels), B = resident fragments.
+    static __device__ __forceinline__ floatx16 rows_times(const char *sub, int lane, const bf16x8 (&resident)[KS])
+    {
+        const int lo = lane & 31, hb = lane >> 5;
+        floatx16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(sub + lo * RowB + (2 * ks + hb) * 16);
+            acc = mfma_32x32x16(a, resident[ks], acc);
+        }
+        return acc;
+    }
+    // acc[db](32 channels x 32 columns) += A B, A = staged sub-block read transposed (rows = channels, k = its 32
+    // tokens in accumulator order), B = the two packed halves of an accumulator.
+    static __device__ __forceinline__ void transposed_times(uint32_t sub_addr, int lane, const bf16x8 (&packed)[2],
+                                                            floatx16 (&acc)[DB])
+    {
+        typedef short shortx8 __attribute__((ext_vector_type(8)));
+        const int hb = lane >> 5, j4 = (lane & 15) >> 2, s4 = lane & 3, blk = (lane >> 4) & 1;
+        const uint32_t base = sub_addr + (uint32_t)((4 * hb + j4) * RowB + (16 * blk + 4 * s4) * 2);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                shortx4 f0, f1;
+                const uint32_t a = base + (uint32_t)(16 * j * RowB + 64 * db);
+                asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %2 offset:%3\n\ts_waitcnt lgkmcnt(0)"
+                             : "=&v"(f0), "=&v"(f1)
+                             : "v"(a), "n"(8 * RowB));
+                const shortx8 a01 = __builtin_shufflevector(f0, f1, 0, 1, 2, 3, 4, 5, 6, 7);
+                acc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, a01), packed[j], acc[db]);
+            }
+    }
+    static __device__ __forceinline__ void load_resident(const bf16_raw *rows, int lane, bf16x8 (&frag)[KS])
+    {
+        const int lo = lane & 31, hb = lane >> 5;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) frag[ks] = *reinterpret_cast<const bf16x8 *>(rows + (size_t)lo * D + ks * 16 + hb * 8);
+    }
+    static __device__ __forceinline__ void store_columns(bf16_raw *dst, int lane, const floatx16 (&acc)[DB], float mul)
+    {
+        const int lo = lane & 31, hb = lane >> 5;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 ov;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) ov[t] = static_cast<__bf16>(acc[db][4 * g + t] * mul);
+                *reinterpret_cast<bf16x4 *>(dst + (size_t)lo * D + db * 32 + g * 8 + hb * 4) = ov;
+            }
+    }
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void sta_bwd_delta_generic_kernel(const uint4 *__restrict__ o,
+                                                                    const uint4 *__restrict__ d_o,
+                                                                    float *__restrict__ delta, size_t rows)
+{
+    constexpr int LPR = D / 8;                     // lanes per row, 16 bytes each
+    const size_t row = (size_t)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+    const int part = threadIdx.x % LPR;
+    float acc = 0.f;
+    if (row < rows) {
+        const uint4 a = o[row * LPR + part], b = d_o[row * LPR + part];
+        const uint32_t as[4] = {a.x, a.y, a.z, a.w}, bs[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc = fmaf(__uint_as_float(as[e] << 16), __uint_as_float(bs[e] << 16), acc);
+            acc = fmaf(__uint_as_float(as[e] & 0xffff0000u), __uint_as_float(bs[e] & 0xffff0000u), acc);
+        }
+    }
+#pragma unroll
+    for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, LPR);
+    if (row < rows && part == 0) delta[row] = acc;
+}
+
+// dQ of 32 queries: grid (N / 32, batch x heads of the launch).
+template <int D>
+__global__ __launch_bounds__(64) void sta_bwd_dq_generic_kernel(const bf16_raw *__restrict__ q,
+                                                                const bf16_raw *__restrict__ k,
+                                                                const bf16_raw *__restrict__ v,
+                                                                const bf16_raw *__restrict__ d_o,
+                                                                const float *__restrict__ lse,
+                                                                const float *__restrict__ delta,
+                                                                bf16_raw *__restrict__ d_q, sta::FwdParams p,
+                                                                sta::WindowTable win)
+{
+    using G = GenericOps<D>;
+    __shared__ __attribute__((aligned(1024))) char smem[2 * G::SubB];         // K, V
+    const uint32_t qblock = blockIdx.x, bh_rank = blockIdx.y;
+    const uint32_t h_local = bh_rank % p.heads, b = bh_rank / p.heads;
+    const size_t bh = (size_t)b * p.H + p.head_base + h_local;
+    const uint32_t q_tile = (qblock * kSub) / p.P;
+    const StaBox box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1], win.w[h_local][2],
+                                           q_tile);
+    const int lane = threadIdx.x, lo = lane & 31;
+    const size_t my_row = bh * p.N + (size_t)qblock * kSub;
+    const char *kh = reinterpret_cast<const char *>(k + bh * p.N * D);
+    const char *vh = reinterpret_cast<const char *>(v + bh * p.N * D);
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
+
+    bf16x8 Qr[G::KS], Gr[G::KS];
+    G::load_resident(q + my_row * D, lane, Qr);
+    G::load_resident(d_o + my_row * D, lane, Gr);
+    const float c = p.scale_log2e;
+    const float lse2 = lse[my_row + lo] * kLog2e;
+    const float dl = delta[my_row + lo];
+    floatx16 dQ[G::DB];
+#pragma unroll
+    for (int db = 0; db < G::DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dQ[db][r] = 0.f;
+
+    BoxWalk walk;
+    walk.start(box, p.n_h, p.n_w, p.P);
+    const int n_iter = box.count() * walk.sub_per_tile;
+    for (int iter = 0; iter < n_iter; ++iter) {
+        __syncthreads();                                   // the previous sub-block has been read
+        G::copy_in(smem, kh + (size_t)walk.next_row * G::RowB, lane);
+        G::copy_in(smem + G::SubB, vh + (size_t)walk.next_row * G::RowB, lane);
+        walk.advance();
+        __syncthreads();
+        const floatx16 S = G::rows_times(smem, lane, Qr);                      // S^T  = K Q^T (keys x queries)
+        const floatx16 dP = G::rows_times(smem + G::SubB, lane, Gr);           // dP^T = V dO^T
+        float ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) ds[r] = __builtin_amdgcn_exp2f(fmaf(S[r], c, -lse2)) * (dP[r] - dl);
+        bf16x8 dSb[2];
+        pack16(ds, dSb);
+        G::transposed_times(smem_addr, lane, dSb, dQ);                         // dQ^T += K^T dS^T
+    }
+    G::store_columns(d_q + my_row * D, lane, dQ, c * kLn2);
+}
+
+// dK and dV of 32 keys: grid (N / 32, batch x heads of the launch); walks the query tiles that keep the key tile.
+template <int D>
+__global__ __launch_bounds__(64) void sta_bwd_dkv_generic_kernel(const bf16_raw *__restrict__ q,
+                                                                 const bf16_raw *__restrict__ k,
+                                                                 const bf16_raw *__restrict__ v,
+                                                                 const bf16_raw *__restrict__ d_o,
+                                                                 const float *__restrict__ lse,
+                                                                 const float *__restrict__ delta,
+                                                                 bf16_raw *__restrict__ d_k,
+                                                                 bf16_raw *__restrict__ d_v, sta::FwdParams p,
+                                                                 sta::WindowTable win)
+{
+    using G = GenericOps<D>;
+    __shared__ __attribute__((aligned(1024))) char smem[2 * G::SubB];         // Q, dO
+    const uint32_t kblock = blockIdx.x, bh_rank = blockIdx.y;
+    const uint32_t h_local = bh_rank % p.heads, b = bh_rank / p.heads;
+    const size_t bh = (size_t)b * p.H + p.head_base + h_local;
+    const uint32_t k_tile = (kblock * kSub) / p.P;
+    const StaBox box = sta_query_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1],
+                                             win.w[h_local][2], k_tile);
+    const int lane = threadIdx.x, hb = lane >> 5;
+    const size_t head_row = bh * p.N;
+    const size_t my_row = head_row + (size_t)kblock * kSub;
+    const char *qh = reinterpret_cast<const char *>(q + head_row * D);
+    const char *gh = reinterpret_cast<const char *>(d_o + head_row * D);
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
+
+    bf16x8 Kr[G::KS], Vr[G::KS];
+    G::load_resident(k + my_row * D, lane, Kr);
+    G::load_resident(v + my_row * D, lane, Vr);
+    const float c = p.scale_log2e;
+    floatx16 dK[G::DB], dV[G::DB];
+#pragma unroll
+    for (int db = 0; db < G::DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            dK[db][r] = 0.f;
+            dV[db][r] = 0.f;
+        }
+
+    BoxWalk walk;
+    walk.start(box, p.n_h, p.n_w, p.P);
+    const int n_iter = box.count() * walk.sub_per_tile;
+    for (int iter = 0; iter < n_iter; ++iter) {
+        __syncthreads();
+        const uint32_t first_row = walk.next_row;
+        G::copy_in(smem, qh + (size_t)first_row * G::RowB, lane);
+        G::copy_in(smem + G::SubB, gh + (size_t)first_row * G::RowB, lane);
+        walk.advance();
+        // statistics of the query rows this lane's accumulator registers belong to: rows 8*g + 4*hb + t
+        float ls[16], dl[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const floatx4 a = *reinterpret_cast<const floatx4 *>(lse + head_row + first_row + 8 * g + 4 * hb);
+            const floatx4 d = *reinterpret_cast<const floatx4 *>(delta + head_row + first_row + 8 * g + 4 * hb);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                ls[4 * g + t] = a[t] * kLog2e;
+                dl[4 * g + t] = d[t];
+            }
+        }
+        __syncthreads();
+        const floatx16 S = G::rows_times(smem, lane, Kr);                      // S  = Q K^T (queries x keys)
+        const floatx16 dP = G::rows_times(smem + G::SubB, lane, Vr);           // dP = dO V^T
+        float prob[16], ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            prob[r] = __builtin_amdgcn_exp2f(fmaf(S[r], c, -ls[r]));
+            ds[r] = prob[r] * (dP[r] - dl[r]);
+        }
+        bf16x8 Pb[2], dSb[2];
+        pack16(prob, Pb);
+        pack16(ds, dSb);
+        G::transposed_times(smem_addr + G::SubB, lane, Pb, dV);                // dV^T += dO^T P
+        G::transposed_times(smem_addr, lane, dSb, dK);                         // dK^T += Q^T dS
+    }
+    G::store_columns(d_v + my_row * D, lane, dV, 1.0f);
+    G::store_columns(d_k + my_row * D, lane, dK, c * kLn2);
+}
+
+template <int D>
+hipError_t launch_backward_generic(const bf16_raw *q, const bf16_raw *k, const bf16_raw *v, const void *o, const void *d_o,
+                                   const float *lse, float *delta, bool compute_delta, void *d_q, void *d_k, void *d_v,
+                                   int B, const sta::FwdParams &p, const sta::WindowTable &win, hipStream_t stream)
+{
+    if (compute_delta) {
+        const size_t rows = (size_t)B * p.H * p.N;   // all heads of the tensor at once
+        const unsigned per_block = 256 / (D / 8);
+        sta_bwd_delta_generic_kernel<D><<<dim3((unsigned)((rows + per_block - 1) / per_block)), dim3(256), 0, stream>>>(
+            static_cast<const uint4 *>(o), static_cast<const uint4 *>(d_o), delta, rows);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const dim3 grid(p.N / kSub, (uint32_t)B * p.heads), block(64);
+    const bf16_raw *gg = static_cast<const bf16_raw *>(d_o);
+    sta_bwd_dq_generic_kernel<D><<<grid, block, 0, stream>>>(q, k, v, gg, lse, delta, static_cast<bf16_raw *>(d_q), p, win);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    sta_bwd_dkv_generic_kernel<D><<<grid, block, 0, stream>>>(q, k, v, gg, lse, delta, static_cast<bf16_raw *>(d_k),
+                                                              static_cast<bf16_raw *>(d_v), p, win);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 namespace sta {
 
-bool backward_supported(int P, int D) { return D == kD && P > 0 && P % kCols == 0; }
+bool backward_supported(int P, int D) { return (D == 64 || D == 128) && P > 0 && P % kSub == 0; }
 
 hipError_t launch_backward(const void *q, const void *k, const void *v, const void *o, const void *d_o, const float *lse,
-                           float *delta, bool compute_delta, void *d_q, void *d_k, void *d_v, int B,
+                           float *delta, bool compute_delta, void *d_q, void *d_k, void *d_v, int B, int D,
                            const FwdParams &p, const WindowTable &win, hipStream_t stream)
 {
-    if (!backward_supported((int)p.P, kD)) return hipErrorInvalidValue;
+    if (!backward_supported((int)p.P, D)) return hipErrorInvalidValue;
     const bf16_raw *qq = static_cast<const bf16_raw *>(q), *kk = static_cast<const bf16_raw *>(k);
     const bf16_raw *vv = static_cast<const bf16_raw *>(v), *gg = static_cast<const bf16_raw *>(d_o);
+    if (D == 64)
+        return launch_backward_generic<64>(qq, kk, vv, o, d_o, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream);
+    if (p.P % kCols != 0 || g_force_generic)
+        return launch_backward_generic<128>(qq, kk, vv, o, d_o, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream);
     if (compute_delta) {
         const size_t rows = (size_t)B * p.H * p.N;   // all heads of the tensor at once
         sta_bwd_delta_kernel<<<dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, stream>>>(

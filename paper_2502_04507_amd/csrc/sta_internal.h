@@ -62,7 +62,7 @@ extern bool g_force_generic;   // debugging aid: route every shape through the g
 // ---- gradients ---------------------------------------------------------------
 // delta: float [B, H, N] scratch (dO_i . O_i per query row), filled by the call when compute_delta is set.
 hipError_t launch_backward(const void *q, const void *k, const void *v, const void *o, const void *d_o, const float *lse,
-                           float *delta, bool compute_delta, void *d_q, void *d_k, void *d_v, int B,
+                           float *delta, bool compute_delta, void *d_q, void *d_k, void *d_v, int B, int D,
                            const FwdParams &p, const WindowTable &win, hipStream_t stream);
 bool backward_supported(int P, int D);
 

@@ -61,7 +61,7 @@ def gpu_backward(w, q, k, v, g, scale=0.0):
 
 
 def oracle_backward(w, q, k, v, g, b, h, scale=None, query_idx=None, key_idx=None):
-    f = lambda x: x[b, h].float().numpy()
+    f = lambda x: x[b, h].to(torch.bfloat16).float().numpy()       # what the kernels see (fp32 inputs are cast)
     return orc.attention_backward(f(q), f(k), f(v), f(g), w.grid, w.tile,
                                   orc.window_tiles_to_tokens(w.window_tiles[h], w.tile), scale=scale,
                                   query_idx=query_idx, key_idx=key_idx)
@@ -88,6 +88,71 @@ def test_backward_parity_whole(name, B, H, grid, tile, windows, scale):
             for label, got, ref in (("dQ", dq, rq), ("dK", dk, rk), ("dV", dv, rv)):
                 st = assert_grad_parity(got[b, h].float().numpy(), ref, "%s %s b%d h%d" % (name, label, b, h))
                 print(name, label, b, h, st)
+
+
+@pytest.mark.parametrize("name,D,grid,tile,windows", [
+    # head dimension 64 with the paper's 384-token tile, and with a 64-token 2D tile
+    ("bwd-d64-p384", 64, (6, 16, 24), (6, 8, 8), [(1, 3, 3), (1, 1, 2)]),
+    ("bwd-d64-p64-2d", 64, (1, 32, 40), (1, 8, 8), [(1, 3, 3), (1, 5, 1)]),
+    # head dimension 128 with tiles that are not multiples of 128 tokens
+    ("bwd-d128-p64", 128, (2, 8, 24), (1, 8, 8), [(3, 1, 3), (1, 1, 1)]),
+    ("bwd-d128-p96", 128, (4, 12, 16), (2, 6, 8), [(1, 3, 1), (3, 3, 3)]),
+])
+def test_backward_parity_general_shapes(name, D, grid, tile, windows):
+    """Head dimension 64 and tiles of 32*k tokens go through the general kernels."""
+    w = syn.custom(name, 1, len(windows), D, grid, tile, windows, "bf16", seed=1210)
+    q, k, v = syn.make_qkv(w)
+    g = syn.make_dout(w)
+    (dq, dk, dv), _ = gpu_backward(w, q, k, v, g)
+    for h in range(w.H):
+        rq, rk, rv = oracle_backward(w, q, k, v, g, 0, h)
+        for label, got, ref in (("dQ", dq, rq), ("dK", dk, rk), ("dV", dv, rv)):
+            print(name, label, h, assert_grad_parity(got[0, h].float().numpy(), ref, "%s %s h%d" % (name, label, h)))
+
+
+@pytest.mark.parametrize("config", ["C1", "C2"])
+def test_backward_parity_small_configs_whole(config):
+    """The two small configurations (3D with fp32 inputs and head dimension 64; 2D image shape, 8 heads), every
+    gradient entry against the oracle."""
+    w = syn.workload(config)
+    q, k, v = syn.make_qkv(w)
+    g = syn.make_dout(w)
+    (dq, dk, dv), _ = gpu_backward(w, q, k, v, g)
+    for h in range(w.H):
+        rq, rk, rv = oracle_backward(w, q, k, v, g, 0, h)
+        for label, got, ref in (("dQ", dq, rq), ("dK", dk, rk), ("dV", dv, rv)):
+            print(config, label, h, assert_grad_parity(got[0, h].float().numpy(), ref, "%s %s h%d" % (config, label, h)))
+
+
+def test_backward_kept_set_read_from_dv():
+    """With Q = 0 every kept key of a query gets the same probability 1/(kept keys), so
+    dV_j = sum over the queries i that keep j of dO_i / (kept keys of i).  With dO one-hot in the channel that is the
+    query's tile id, dV_j[c] * (kept keys of tile c) = (queries of tile c that keep j) = P if tile c keeps tile j, else
+    0: the transposed key-tile set, read exactly (every value is a small integer multiple of a power of two only when
+    the kept count is; so the test compares against the oracle's box with a tolerance far below one token)."""
+    for D, grid, tile, window in ((128, (4, 16, 16), (2, 8, 8), (3, 1, 3)), (64, (1, 24, 40), (1, 8, 8), (1, 3, 5)),
+                                  (128, (6, 16, 24), (6, 8, 8), (1, 3, 2))):
+        w = syn.custom("bwd-kept", 1, 1, D, grid, tile, [window], "bf16", seed=1)
+        assert w.n_tiles <= D
+        counts, lists = orc.key_tiles(w.grid, w.tile, orc.window_tiles_to_tokens(window, w.tile))
+        z = torch.zeros((1, 1, w.N, D), dtype=torch.bfloat16)
+        v = torch.ones_like(z)
+        g = torch.zeros_like(z)
+        order = orc.tile_order(w.grid, w.tile)
+        tile_of_raster = np.empty(w.N, dtype=np.int64)
+        tile_of_raster[order] = np.repeat(np.arange(w.n_tiles), w.P)
+        g[0, 0, torch.arange(w.N), torch.from_numpy(tile_of_raster)] = 1.0
+        (_, _, dv), _ = gpu_backward(w, z, z.clone(), v, g)
+        dv = dv[0, 0].float().numpy()[order].reshape(w.n_tiles, w.P, D)       # [key tile, key in tile, channel]
+        keeps = np.zeros((w.n_tiles, w.n_tiles), dtype=bool)                  # keeps[c, j]: query tile c keeps key tile j
+        for c in range(w.n_tiles):
+            keeps[c, lists[c][:counts[c]]] = True
+        for j in range(w.n_tiles):
+            want = np.where(keeps[:, j], w.P / (counts.astype(np.float64) * w.P), 0.0)   # P queries x 1/(kept keys)
+            got = dv[j][:, :w.n_tiles]
+            assert np.allclose(got, want[None, :], rtol=2.0 ** -7, atol=0), (D, grid, j)
+            assert (got[:, ~keeps[:, j]] == 0).all(), (D, grid, j)
+        assert (dv[:, :, w.n_tiles:] == 0).all()
 
 
 def test_backward_many_heads_in_chunks():
@@ -150,10 +215,10 @@ def test_backward_errors():
     with pytest.raises(sta.StaError) as e:       # two outputs alias
         sta.sta_backward(qt, kt, vt, ot, gt, lse, dq, dq, dv, w.grid, w.tile, w.window_tiles, ws)
     assert e.value.status == 5
-    # head dimension 64 and a 64-token tile have no gradient kernel
-    t64 = lambda: torch.zeros((1, 1, 64, 64), dtype=torch.bfloat16, device=DEV)
-    a = [t64() for _ in range(8)]
+    # a tile that is not a multiple of 32 tokens has no gradient kernel
+    t48 = lambda: torch.zeros((1, 1, 48, 64), dtype=torch.bfloat16, device=DEV)
+    a = [t48() for _ in range(8)]
     with pytest.raises(sta.StaError) as e:
-        sta.sta_backward(*a[:5], torch.zeros((1, 1, 64), dtype=torch.float32, device=DEV), *a[5:], (1, 8, 8), (1, 8, 8),
+        sta.sta_backward(*a[:5], torch.zeros((1, 1, 48), dtype=torch.float32, device=DEV), *a[5:], (1, 6, 8), (1, 6, 8),
                          [(1, 1, 1)], ws)
     assert e.value.status == 4
