@@ -14,8 +14,8 @@
  *     n = (t*grid[1] + h)*grid[2] + w.  "tiled" order puts it at
  *     n = tile_id*P + intra_id with tile_id row-major over the tile grid
  *     (grid[a]/tile[a] per axis), intra_id row-major inside the tile and
- *     P = tile[0]*tile[1]*tile[2]  (Sec. 3.1: tokens of one tile get
- *     consecutive sequence indices; appendix "Tiling in STA").
+ *     P = tile[0]*tile[1]*tile[2]  (Sec. 3.1: each tile occupies one
+ *     contiguous run of the sequence; appendix "Tiling in STA").
  *   - All device work is enqueued on `hip_stream` (a hipStream_t passed as
  *     void*, NULL = default stream) and is asynchronous.
  *   - The library allocates no device memory and keeps no state.

@@ -26,9 +26,9 @@
  *                           backward formula; this is the chain rule applied
  *                           to Eq. 1, step by step, in fp64.
  *   - sta_oracle_tile_order / _tile_permute / _untile:
- *                           the tile-contiguous token order of Sec. 3.1
- *                           ("tokens within the same tile have consecutive
- *                           sequence indices") and appendix "Tiling in STA".
+ *                           the tile-contiguous token order of Sec. 3.1 (the
+ *                           tokens of a tile occupy one run of the sequence)
+ *                           and appendix "Tiling in STA".
  *   - sta_oracle_key_tiles: key-tile list of every query tile, obtained by
  *                           collapsing the token predicate (first token of
  *                           each tile).

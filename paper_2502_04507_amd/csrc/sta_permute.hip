@@ -1,7 +1,7 @@
 // Tile / untile permutation kernels (HBM-bound).
 //
-// STA orders tokens so that the tokens of one (T_t, T_h, T_w) tile have
-// consecutive sequence indices (Sec. 3.1; appendix "Tiling in STA").  In
+// STA orders tokens so that each (T_t, T_h, T_w) tile occupies one contiguous
+// run of the sequence (Sec. 3.1; appendix "Tiling in STA").  In
 // raster order a tile is T_t*T_h runs of T_w consecutive tokens, so both sides
 // of the copy are made of contiguous segments of T_w*D elements: one
 // workgroup moves one tile of one (batch, head) slice, each lane moving 8
