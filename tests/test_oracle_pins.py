@@ -485,6 +485,31 @@ def test_fig3_block_types_for_the_three_orderings():
     assert orc.block_census(grid, tile, win)[:2] == (sd.sum(), 0)
 
 
+def test_raster_block_census_on_countable_cases():
+    """The raster-order census (blocks of P consecutive raster tokens) on cases that can be counted by hand.
+    (a) In 1-D raster order and tile order are the same order, so both censuses agree block by block, for both masks
+    (the tiled one is pinned to Theorem 1 above).  (b) A window that covers the whole grid keeps every pair: every
+    block is dense in any order.  (c) Image 2 x 8, tile 2 x 2 (P = 4), STA window of one tile: a raster block is half
+    an image row, i.e. the top (or bottom) halves of two tiles; each of its queries keeps the two columns of its own
+    tile in both rows, so the block meets the two half-row key blocks of its own image half partially (mixed), the
+    other two not at all, and none completely."""
+    for T, W, n in ((4, 5, 9), (3, 9, 8), (8, 3, 5)):
+        grid, tile, win = (1, 1, n * T), (1, 1, T), (1, 1, W)
+        for mask in ("sta", "natten"):
+            rd, rm = orc.block_census_per_query(mask, "raster", grid, tile, win)
+            td, tm = orc.block_census_per_query(mask, "tiled", grid, tile, win)
+            assert (rd == td).all() and (rm == tm).all(), (mask, T, W)
+    grid, tile = (2, 4, 6), (1, 2, 3)
+    for mask in ("sta", "natten"):
+        for order in ("raster", "tiled"):
+            d, m = orc.block_census_per_query(mask, order, grid, tile, (3, 9, 11))     # covers 2 x 4 x 6 from anywhere
+            assert (d == 8).all() and (m == 0).all(), (mask, order)
+    d, m = orc.block_census_per_query("sta", "raster", (1, 2, 8), (1, 2, 2), (1, 2, 2))
+    assert d.tolist() == [0, 0, 0, 0] and m.tolist() == [2, 2, 2, 2]
+    d, m = orc.block_census_per_query("sta", "tiled", (1, 2, 8), (1, 2, 2), (1, 2, 2))
+    assert d.tolist() == [1, 1, 1, 1] and m.tolist() == [0, 0, 0, 0]
+
+
 # ---- gradients of Eq. 1 under the STA mask ---------------------------------------------------------------
 
 def _autograd_dense(q, k, v, g, scale, additive_mask=None):
