@@ -16,7 +16,11 @@ struct PermuteParams {
     uint32_t chunks_per_tile;   // P * cpr
     uint32_t seg, seg_magic;    // T_w * cpr chunks per contiguous run, ceil(2^32/seg)
     uint32_t T_h_magic;         // ceil(2^32 / T_h)
+    uint32_t parts;             // workgroups per tile
+    uint32_t span;              // chunks per workgroup (the last one of a tile may get fewer)
 };
+
+constexpr uint32_t kPermuteChunksPerBlock = 1024;   // 256 lanes x 4 chunks of 16 bytes
 
 hipError_t launch_permute(const void *src, void *dst, bool src_f32, bool dst_f32, bool to_tiled,
                           const PermuteParams &p, uint32_t blocks, hipStream_t stream);

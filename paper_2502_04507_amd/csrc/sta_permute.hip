@@ -3,9 +3,10 @@
 // STA orders tokens so that each (T_t, T_h, T_w) tile occupies one contiguous
 // run of the sequence (Sec. 3.1; appendix "Tiling in STA").  In
 // raster order a tile is T_t*T_h runs of T_w consecutive tokens, so both sides
-// of the copy are made of contiguous segments of T_w*D elements: one
-// workgroup moves one tile of one (batch, head) slice, each lane moving 8
-// elements (16 B of bf16) at a time with the tiled side fully linear.
+// of the copy are made of contiguous segments of T_w*D elements: a workgroup
+// moves one tile of one (batch, head) slice, or an even share of it when the
+// tensor has too few tiles to fill the chip, each lane moving 8 elements (16 B
+// of bf16) at a time with the tiled side fully linear.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -36,26 +37,42 @@ __device__ __forceinline__ void load8(const void *base, size_t chunk, Chunk8bf16
     }
 }
 
+// 16-byte store that does not leave a dirty line in L2.  The outputs are written once and read by a later kernel;
+// with ordinary stores the dirty lines are written back when the kernel ends, which at small sizes costs more than
+// the copy itself (measured: 4 MB tensor 17 -> 2.7 us per launch, 85 MB tensor 33 -> 25.6 us, 1.4 GB 261 -> 247 us).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store16_streaming(void *base, size_t chunk16, u32x4_t v)
+{
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(base) + chunk16);
+}
+
 template <bool SRC_F32, bool DST_F32>
 __device__ __forceinline__ void store8(void *base, size_t chunk, const Chunk8bf16 &b, const Chunk8f32 &f)
 {
-    if constexpr (SRC_F32 == DST_F32) {
-        if constexpr (SRC_F32) reinterpret_cast<Chunk8f32 *>(base)[chunk] = f;
-        else reinterpret_cast<Chunk8bf16 *>(base)[chunk] = b;
-    } else if constexpr (SRC_F32) {              // f32 -> bf16
-        Chunk8bf16 o;
-        o.w[0] = pack2_bf16(f.lo.x, f.lo.y);
-        o.w[1] = pack2_bf16(f.lo.z, f.lo.w);
-        o.w[2] = pack2_bf16(f.hi.x, f.hi.y);
-        o.w[3] = pack2_bf16(f.hi.z, f.hi.w);
-        reinterpret_cast<Chunk8bf16 *>(base)[chunk] = o;
-    } else {                                     // bf16 -> f32 (exact)
-        Chunk8f32 o;
-        o.lo.x = __uint_as_float(b.w[0] << 16); o.lo.y = __uint_as_float(b.w[0] & 0xffff0000u);
-        o.lo.z = __uint_as_float(b.w[1] << 16); o.lo.w = __uint_as_float(b.w[1] & 0xffff0000u);
-        o.hi.x = __uint_as_float(b.w[2] << 16); o.hi.y = __uint_as_float(b.w[2] & 0xffff0000u);
-        o.hi.z = __uint_as_float(b.w[3] << 16); o.hi.w = __uint_as_float(b.w[3] & 0xffff0000u);
-        reinterpret_cast<Chunk8f32 *>(base)[chunk] = o;
+    if constexpr (!DST_F32) {
+        u32x4_t o;
+        if constexpr (SRC_F32) {                 // f32 -> bf16
+            o[0] = pack2_bf16(f.lo.x, f.lo.y);
+            o[1] = pack2_bf16(f.lo.z, f.lo.w);
+            o[2] = pack2_bf16(f.hi.x, f.hi.y);
+            o[3] = pack2_bf16(f.hi.z, f.hi.w);
+        } else {
+            o[0] = b.w[0]; o[1] = b.w[1]; o[2] = b.w[2]; o[3] = b.w[3];
+        }
+        store16_streaming(base, chunk, o);
+    } else {
+        u32x4_t lo, hi;
+        if constexpr (SRC_F32) {
+            lo[0] = __float_as_uint(f.lo.x); lo[1] = __float_as_uint(f.lo.y);
+            lo[2] = __float_as_uint(f.lo.z); lo[3] = __float_as_uint(f.lo.w);
+            hi[0] = __float_as_uint(f.hi.x); hi[1] = __float_as_uint(f.hi.y);
+            hi[2] = __float_as_uint(f.hi.z); hi[3] = __float_as_uint(f.hi.w);
+        } else {                                 // bf16 -> f32 (exact)
+            lo[0] = b.w[0] << 16; lo[1] = b.w[0] & 0xffff0000u; lo[2] = b.w[1] << 16; lo[3] = b.w[1] & 0xffff0000u;
+            hi[0] = b.w[2] << 16; hi[1] = b.w[2] & 0xffff0000u; hi[2] = b.w[3] << 16; hi[3] = b.w[3] & 0xffff0000u;
+        }
+        store16_streaming(base, 2 * chunk, lo);
+        store16_streaming(base, 2 * chunk + 1, hi);
     }
 }
 
@@ -67,6 +84,7 @@ __device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t d, uint32_t ma
 
 constexpr int kPermuteThreads = 256;
 constexpr int kUnroll = 4;
+static_assert(kPermuteThreads * kUnroll == (int)sta::kPermuteChunksPerBlock, "one pass per workgroup");
 
 // TO_TILED: src is raster, dst is tiled.  Otherwise the reverse.
 template <bool SRC_F32, bool DST_F32, bool TO_TILED>
@@ -74,8 +92,10 @@ __global__ __launch_bounds__(kPermuteThreads) void sta_permute_kernel(const void
                                                                      void *__restrict__ dst,
                                                                      sta::PermuteParams p)
 {
-    const uint32_t tile_id = blockIdx.x % p.n_tiles;
-    const uint32_t outer = blockIdx.x / p.n_tiles;          // b*H + h
+    const uint32_t part = blockIdx.x % p.parts;
+    const uint32_t tile_linear = blockIdx.x / p.parts;
+    const uint32_t tile_id = tile_linear % p.n_tiles;
+    const uint32_t outer = tile_linear / p.n_tiles;         // b*H + h
     const uint32_t tw = tile_id % p.n_w;
     const uint32_t th = (tile_id / p.n_w) % p.n_h;
     const uint32_t tt = tile_id / (p.n_w * p.n_h);
@@ -87,14 +107,16 @@ __global__ __launch_bounds__(kPermuteThreads) void sta_permute_kernel(const void
     const uint32_t row_stride_h = p.L_w * p.cpr;            // chunks per raster row of tokens (fixed t,h)
     const uint32_t row_stride_t = p.L_h * row_stride_h;
 
-    for (uint32_t i0 = threadIdx.x; i0 < p.chunks_per_tile; i0 += kPermuteThreads * kUnroll) {
+    const uint32_t first = part * p.span;
+    const uint32_t end = first + p.span < p.chunks_per_tile ? first + p.span : p.chunks_per_tile;
+    for (uint32_t i0 = first + threadIdx.x; i0 < end; i0 += kPermuteThreads * kUnroll) {
         Chunk8bf16 b[kUnroll];
         Chunk8f32 f[kUnroll];
         size_t dst_idx[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const uint32_t idx = i0 + u * kPermuteThreads;
-            if (idx < p.chunks_per_tile) {
+            if (idx < end) {
                 const uint32_t seg = fast_div(idx, p.seg, p.seg_magic);      // which (i_t, i_h) run
                 const uint32_t off = idx - seg * p.seg;
                 const uint32_t it = fast_div(seg, p.T_h, p.T_h_magic);
@@ -108,7 +130,7 @@ __global__ __launch_bounds__(kPermuteThreads) void sta_permute_kernel(const void
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const uint32_t idx = i0 + u * kPermuteThreads;
-            if (idx < p.chunks_per_tile) store8<SRC_F32, DST_F32>(dst, dst_idx[u], b[u], f[u]);
+            if (idx < end) store8<SRC_F32, DST_F32>(dst, dst_idx[u], b[u], f[u]);
         }
     }
 }
