@@ -60,7 +60,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C4", help="C1..C5 or C4dense")
+    ap.add_argument("--workload", default="C4", help="C1..C5, C4dense, or the head-dimension-64 shapes D64-2D, D64-3D")
     ap.add_argument("--window", default=None, help="override: uniform window in tiles, e.g. 3,3,3")
     ap.add_argument("--calls", type=int, default=30, help="event-timed calls per entry point (at least 30)")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense (full-window) comparison run and the sweep")
@@ -422,7 +422,7 @@ def main():
                 "speedup_sparse_vs_dense": dense["ms"] / fwd_ms, "ideal_speedup": same[0]["ideal_speedup"],
                 "kernel_efficiency": fwd_tflops / dense["tflops"],
             }
-        for name in ("C1", "C2", "C3"):
+        for name in ("C1", "C2", "C3", "D64-2D", "D64-3D"):
             wl = syn.workload(name)
             other = Layer(wl, device)
             other.permute_in()

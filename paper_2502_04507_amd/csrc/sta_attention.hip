@@ -301,30 +301,39 @@ __device__ __forceinline__ FwdItem fwd_item_of(uint32_t id, const sta::FwdParams
 // items from `split_first` on into `split_parts` workgroups each; part j walks the sub-blocks
 // [n*j/parts, n*(j+1)/parts) of the item's key walk and leaves its unnormalised accumulator, exponent offset and
 // row sum in the workspace, and sta_fwd_combine_kernel merges the parts of an item in a fixed order.
-// Workspace layout, per part (index = workgroup id - split_first): float O[QB][128], float m[QB], float l[QB].
-__device__ __forceinline__ size_t split_part_floats(int QB) { return (size_t)QB * 130; }
+// Workspace layout, per part (index = workgroup id - split_first): float O[QB][D], float m[QB], float l[QB].
+template <int D>
+__host__ __device__ __forceinline__ size_t split_part_floats(int QB) { return (size_t)QB * (D + 2); }
 
 // ---------------------------------------------------------------------------
-// Fast path: head dim 128.  NW waves x 32 queries per workgroup (one query block per wave; at least two waves
+// Fast path: head dim 128 or 64.  NW waves x 32 queries per workgroup (one query block per wave; at least two waves
 // per SIMD on a CU, so one wave's softmax overlaps another's MFMAs), K/V sub-blocks of KB keys DMA'd
 // HBM/L2 -> LDS with global_load_lds (no staging registers), STAGES-deep, one barrier per sub-block.  LDS holds
-// K and V row-major, 256 B per key, with the 16-byte chunks of each row XOR-swizzled so that both the b128
+// K and V row-major, 2*D bytes per key, with the 16-byte chunks of each row XOR-swizzled so that both the b128
 // K-operand reads and the transposing ds_read_b64_tr_b16 V-operand reads are bank-conflict free:
-//   K: chunk c of row r is stored at chunk position c ^ (r & 15)
-//   V: chunk c of row r is stored at chunk position c ^ ((r & 3) << 2)
+//   D = 128 (a row spans all 64 banks):  K: chunk c of row r sits at position c ^ (r & 15)
+//                                        V: chunk c of row r sits at position c ^ ((r & 3) << 2)
+//   D = 64 (two rows span the banks):    K: c ^ ((r >> 1) & 7)      V: c ^ (((r >> 1) & 1) << 2)
+// (16 lanes of a b128 read take rows r..r+15 at one logical chunk: they must land on 16 different 16-byte bank
+// groups; 32 lanes of a transposing read take 4 rows x 4 consecutive chunks: likewise.)
 // Instances in use: <12, 32, 2, 1> (384-token tiles: one 12-wave workgroup per query tile and per CU) and
 // <4, 32, 2, 3> (other tile sizes that are multiples of 128: three 4-wave workgroups per CU; 32-key sub-blocks
 // measured 3-5 % faster than 64-key ones in this shape).
 // ---------------------------------------------------------------------------
-template <int NW, int KB, int STAGES, int MINB>
-__global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_raw *__restrict__ q,
+template <int D>
+__device__ __forceinline__ constexpr int k_swizzle(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+template <int D>
+__device__ __forceinline__ constexpr int v_swizzle(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
+
+template <int D, int NW, int KB, int STAGES, int MINB>
+__global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_raw *__restrict__ q,
                                                                  const bf16_raw *__restrict__ k,
                                                                  const bf16_raw *__restrict__ v,
                                                                  bf16_raw *__restrict__ o, sta::FwdParams p,
                                                                  sta::WindowTable win, sta::HeadOrder order,
                                                                  uint32_t n_bh)
 {
-    constexpr int D = 128;
+    static_assert(D == 128 || D == 64, "head dimension");
     constexpr int QB = NW * 32;                    // queries per workgroup: one 32-query block per wave
     constexpr int MB = KB / 32;
     constexpr int KS = D / 16;
@@ -333,9 +342,14 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     constexpr int TILE_BYTES = KB * ROWB;          // one K (or V) sub-block
     constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // K then V
     constexpr int INSTR = TILE_BYTES / 1024;       // 1 KB DMA instructions per operand per sub-block
-    constexpr int LOADERS = NW < 8 ? 4 : 8;        // waves 0 .. LOADERS-1 issue the DMA
+    constexpr int WANT_LOADERS = NW < 4 ? NW : (NW < 8 ? 4 : 8);
+    constexpr int LOADERS = WANT_LOADERS < INSTR ? WANT_LOADERS : INSTR;     // waves 0 .. LOADERS-1 issue the DMA
     constexpr int LOADS = INSTR / LOADERS;         // ... this many instructions per operand each
-    static_assert(KB % 32 == 0 && INSTR % LOADERS == 0 && LOADS >= 1 && LOADERS <= NW, "sub-block shape");
+    constexpr int RPI = 1024 / ROWB;               // key rows per DMA instruction (4 or 8)
+    constexpr int IPB = 16 / RPI;                  // DMA instructions per block of 16 rows
+    constexpr int LPR = ROWB / 16;                 // lanes (16-byte chunks) per row
+    static_assert(KB % 32 == 0 && INSTR % LOADERS == 0 && LOADS >= 1 && LOADERS <= NW && LOADERS % IPB == 0,
+                  "sub-block shape");
     static_assert(STAGES >= 2 && STAGES <= 4, "LDS stages");
 
     __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_BYTES];
@@ -366,19 +380,19 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     const char *kh = reinterpret_cast<const char *>(k + bh * p.N * D);
     const char *vh = reinterpret_cast<const char *>(v + bh * p.N * D);
 
-    // ---- DMA loads.  Each wave-wide 16 B/lane instruction fills 1 KB of LDS = 4 consecutive key rows (a lane's
-    // LDS slot is fixed by the hardware: base + 16*lane), so the swizzle is applied on the global side: the lane
-    // fetches the logical chunk that belongs at its slot.  The KB keys of a sub-block are taken as blocks of 16
-    // rows; loading wave w fetches rows 4*(w&3) .. +3 of the blocks LOADS*(w>>2) .. +LOADS-1, one instruction per
-    // block.  Both swizzles depend on the row only through row & 15, so a lane's offset inside its block is the
-    // same for all its instructions and the rest of the address is wave-uniform: one 32-bit lane offset per
-    // operand on top of a scalar base, and no vector arithmetic per load.
+    // ---- DMA loads.  Each wave-wide 16 B/lane instruction fills 1 KB of LDS = RPI consecutive key rows (a
+    // lane's LDS slot is fixed by the hardware: base + 16*lane), so the swizzle is applied on the global side: the
+    // lane fetches the logical chunk that belongs at its slot.  The KB keys of a sub-block are taken as blocks of
+    // 16 rows; loading wave w fetches rows RPI*(w%IPB) .. +RPI-1 of the blocks LOADS*(w/IPB) .. +LOADS-1, one
+    // instruction per block.  Both swizzles depend on the row only through row & 15, so a lane's offset inside
+    // its block is the same for all its instructions and the rest of the address is wave-uniform: one 32-bit
+    // lane offset per operand on top of a scalar base, and no vector arithmetic per load.
     uint32_t k_lane_off, v_lane_off;
     {
-        const int lrow = 4 * (wave & 3) + (lane >> 4);      // row & 15 of every row this lane fetches
-        const int slot = lane & 15;
-        k_lane_off = (uint32_t)(lrow * ROWB + ((slot ^ lrow) << 4));
-        v_lane_off = (uint32_t)(lrow * ROWB + ((slot ^ ((lrow & 3) << 2)) << 4));
+        const int lrow = RPI * (wave % IPB) + lane / LPR;   // row & 15 of every row this lane fetches
+        const int slot = lane % LPR;
+        k_lane_off = (uint32_t)(lrow * ROWB + ((slot ^ k_swizzle<D>(lrow)) << 4));
+        v_lane_off = (uint32_t)(lrow * ROWB + ((slot ^ v_swizzle<D>(lrow)) << 4));
     }
     auto issue_loads = [&](int stage, size_t key_byte_base) {
         char *sdst = smem + stage * STAGE_BYTES;                           // only waves < LOADERS get here
@@ -386,9 +400,9 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
         asm volatile("" : "+v"(koff), "+v"(voff));      // keep the lane offsets 32-bit next to a scalar base
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
-            const int block16 = LOADS * (wave >> 2) + i;
+            const int block16 = LOADS * (wave / IPB) + i;
             const size_t gbase = key_byte_base + (size_t)block16 * (16 * ROWB);
-            char *kdst = sdst + (16 * block16 + 4 * (wave & 3)) * ROWB;
+            char *kdst = sdst + (16 * block16 + RPI * (wave % IPB)) * ROWB;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + gbase + koff),
                                              STA_LDS_PTR(kdst), 16, 0, 0);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + gbase + voff),
@@ -401,7 +415,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
     uint32_t k_addr[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) k_addr[ks] = smem_addr + (uint32_t)(lo * ROWB + (((2 * ks + hb) ^ (lo & 15)) << 4));
+    for (int ks = 0; ks < KS; ++ks) k_addr[ks] = smem_addr + (uint32_t)(lo * ROWB + (((2 * ks + hb) ^ k_swizzle<D>(lo)) << 4));
     // V (A operand of O^T += V^T P^T) through the transposing read: within each block of 16 lanes, lane
     // r = 4*j4 + s supplies 4 channels (4*s..4*s+3 of the block's 16) of key row j4; lane i then receives
     // channel i of rows 0..3.
@@ -409,7 +423,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     uint32_t v_addr[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
-        v_addr[db] = smem_addr + (uint32_t)((4 * hb + j4) * ROWB + ((((db ^ j4) << 2) | (2 * blk + (s4 >> 1))) << 4) + 8 * (s4 & 1));
+        v_addr[db] = smem_addr + (uint32_t)((4 * hb + j4) * ROWB +
+                                            (((4 * db + 2 * blk + (s4 >> 1)) ^ v_swizzle<D>(4 * hb + j4)) << 4) + 8 * (s4 & 1));
 
     // ---- Q fragments (B operand of S^T), resident in registers
     bf16x8 Qr[KS];
@@ -528,12 +543,13 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
 #pragma unroll
             for (int r = 0; r < 16; ++r) S[mb][r] = 0.f;
         bf16x8 ka[2][4];
-        k_issue<0, ROWB, KOFF>(ka[0], k_addr);
-        static_for<0, MB * 2>([&](auto gi) {
+        constexpr int GPM = KS / 4;                 // groups of four k-steps per 32-key block
+        k_issue<0, ROWB, KOFF, GPM>(ka[0], k_addr);
+        static_for<0, MB * GPM>([&](auto gi) {
             constexpr int g = decltype(gi)::value;
-            constexpr int mb = g / 2, ks0 = 4 * (g % 2);
-            if constexpr (g + 1 < MB * 2) {
-                k_issue<g + 1, ROWB, KOFF>(ka[(g + 1) & 1], k_addr);
+            constexpr int mb = g / GPM, ks0 = 4 * (g % GPM);
+            if constexpr (g + 1 < MB * GPM) {
+                k_issue<g + 1, ROWB, KOFF, GPM>(ka[(g + 1) & 1], k_addr);
                 k_wait<4>(ka[g & 1]);
             } else {
                 k_wait<0>(ka[g & 1]);
@@ -622,7 +638,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
     const float l_tot = half_swap_sum(l_run);
     if (is_part) {
         // unnormalised accumulator, offset and row sum of this part; the combine kernel does the rest
-        float *ws = p.split_ws + (size_t)(blockIdx.x - p.split_first) * split_part_floats(QB);
+        float *ws = p.split_ws + (size_t)(blockIdx.x - p.split_first) * split_part_floats<D>(QB);
         float *wo = ws + (size_t)(wave * 32 + lo) * D;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -657,23 +673,23 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_d128_kernel(const bf16_
 
 // Merges the parts of every split item: one wave per query row, two channels per lane.  With m the largest of
 // the parts' offsets:  O = sum_j 2^((m_j - m) c) O_j / sum_j 2^((m_j - m) c) l_j, parts taken in ascending order.
-template <int QB>
+template <int D, int QB>
 __global__ __launch_bounds__(256) void sta_fwd_combine_kernel(bf16_raw *__restrict__ o, sta::FwdParams p,
                                                               sta::HeadOrder order, uint32_t n_bh)
 {
-    constexpr int D = 128;
+    static_assert(D == 128, "two channels per lane");
     const uint32_t item_id = p.split_first + blockIdx.y;
     const FwdItem item = fwd_item_of<QB>(item_id, p, order, n_bh);
     if (!item.valid) return;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);       // query inside the block
     const int lane = threadIdx.x & 63;
-    const float *ws = p.split_ws + (size_t)blockIdx.y * p.split_parts * split_part_floats(QB);
+    const float *ws = p.split_ws + (size_t)blockIdx.y * p.split_parts * split_part_floats<D>(QB);
     const float c = p.scale_log2e;
     float m = -INFINITY;
-    for (uint32_t j = 0; j < p.split_parts; ++j) m = fmaxf(m, ws[j * split_part_floats(QB) + (size_t)QB * D + row]);
+    for (uint32_t j = 0; j < p.split_parts; ++j) m = fmaxf(m, ws[j * split_part_floats<D>(QB) + (size_t)QB * D + row]);
     float l = 0.f, a0 = 0.f, a1 = 0.f;
     for (uint32_t j = 0; j < p.split_parts; ++j) {
-        const float *part = ws + j * split_part_floats(QB);
+        const float *part = ws + j * split_part_floats<D>(QB);
         const float w = exp2f((part[(size_t)QB * D + row] - m) * c);
         l += w * part[(size_t)QB * D + QB + row];
         const float2 x = *reinterpret_cast<const float2 *>(part + (size_t)row * D + 2 * lane);
@@ -704,8 +720,8 @@ inline uint32_t resident_workgroups(int minb)
     return (uint32_t)cus * (uint32_t)minb;
 }
 
-template <int NW, int KB, int STAGES, int MINB>
-hipError_t launch_fast_d128(const void *q, const void *k, const void *v, void *o, int B, const sta::FwdParams &p_in,
+template <int D, int NW, int KB, int STAGES, int MINB>
+hipError_t launch_fast(const void *q, const void *k, const void *v, void *o, int B, const sta::FwdParams &p_in,
                             const sta::WindowTable &win, const sta::HeadOrder &order, float *split_ws,
                             size_t split_ws_floats, hipStream_t stream)
 {
@@ -719,7 +735,7 @@ hipError_t launch_fast_d128(const void *q, const void *k, const void *v, void *o
     p.split_parts = 1;
     p.split_ws = nullptr;
     uint32_t split_items = 0;
-    if (split_ws != nullptr) {
+    if (D == 128 && split_ws != nullptr) {
         // Items beyond the last full round of workgroups are split so that their parts fill the chip once.
         auto names_item = [&](uint32_t id) {
             const uint32_t xcd = id & 7, slot = id >> 3;
@@ -750,7 +766,7 @@ hipError_t launch_fast_d128(const void *q, const void *k, const void *v, void *o
                 --first;
                 if (names_item(first)) ++found;
             }
-            const size_t need = (size_t)(ids - first) * parts * ((size_t)QB * 130);
+            const size_t need = (size_t)(ids - first) * parts * split_part_floats<D>(QB);
             if (parts > 1 && found == tail && need <= split_ws_floats) {
                 p.split_first = first;
                 p.split_parts = parts;
@@ -760,13 +776,17 @@ hipError_t launch_fast_d128(const void *q, const void *k, const void *v, void *o
         }
     }
     dim3 grid(p.split_first + split_items * p.split_parts), block(NW * 64);
-    sta_fwd_d128_kernel<NW, KB, STAGES, MINB><<<grid, block, 0, stream>>>(
+    sta_fwd_fast_kernel<D, NW, KB, STAGES, MINB><<<grid, block, 0, stream>>>(
         static_cast<const bf16_raw *>(q), static_cast<const bf16_raw *>(k), static_cast<const bf16_raw *>(v),
         static_cast<bf16_raw *>(o), p, win, order, n_bh);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split_items == 0) return e;
-    sta_fwd_combine_kernel<QB><<<dim3(QB / 4, split_items), dim3(256), 0, stream>>>(static_cast<bf16_raw *>(o), p, order, n_bh);
-    return hipGetLastError();
+    if constexpr (D == 128) {
+        sta_fwd_combine_kernel<D, QB><<<dim3(QB / 4, split_items), dim3(256), 0, stream>>>(static_cast<bf16_raw *>(o), p, order, n_bh);
+        return hipGetLastError();
+    } else {
+        return hipErrorInvalidValue;      // head dimension 64 is never split (the caller passes no workspace)
+    }
 }
 
 // Test hook: the key-tile list of every (head, query tile) from the same box function.
@@ -834,15 +854,27 @@ hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, 
                           hipStream_t stream)
 {
     if (!forward_supported((int)p.P, D)) return hipErrorInvalidValue;
-    if (D == 64) return launch_d<64>(q, k, v, o, B, p, win, stream);
+    if (D == 64) {
+        // Head dimension 64: the same kernel with 128-byte rows.  Measured (24 heads, 30x48x80, window 3x3x3):
+        // 12 waves with 64-key sub-blocks 1003 TFLOP/s, with 32-key sub-blocks 909; the register-staged general
+        // kernel 459.  64-token tiles (2D images) get 2-wave workgroups: 575 TFLOP/s on 128 heads of a 64x64 image
+        // (32-key sub-blocks, 2 stages; 64-key sub-blocks 501, 3 stages 537; general kernel 237).  That shape moves
+        // 147 KB of K and V from L2 per 9.4 MFLOP work item, about 9 TB/s at this rate: it is bound by L2, not MFMA.
+        if (!sta::g_force_generic) {
+            if (p.P % 384 == 0) return launch_fast<64, 12, 64, 2, 1>(q, k, v, o, B, p, win, order, nullptr, 0, stream);
+            if (p.P % 128 == 0) return launch_fast<64, 4, 64, 2, 3>(q, k, v, o, B, p, win, order, nullptr, 0, stream);
+            if (p.P % 64 == 0) return launch_fast<64, 2, 32, 2, 3>(q, k, v, o, B, p, win, order, nullptr, 0, stream);
+        }
+        return launch_d<64>(q, k, v, o, B, p, win, stream);
+    }
     // A tile of 384 tokens (the paper's 6x8x8) gets one 12-wave workgroup per query tile: every K/V sub-block
     // fetched from L2 then serves 384 queries instead of 128.  Measured at the 115,200-token layer, window
     // 3x3x3: 12.8-13.1 ms against 13.6-13.7 ms for the 4-wave shape in the same session; 2 LDS stages were
     // faster than 3 (13.15 ms) or 4 (13.3 ms).
     if (p.P % 384 == 0 && !sta::g_force_generic)
-        return launch_fast_d128<12, 32, 2, 1>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
+        return launch_fast<128, 12, 32, 2, 1>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
     if (p.P % 128 == 0 && !sta::g_force_generic)
-        return launch_fast_d128<4, 32, 2, 3>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
+        return launch_fast<128, 4, 32, 2, 3>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
     return launch_d<128>(q, k, v, o, B, p, win, stream);
 }
 

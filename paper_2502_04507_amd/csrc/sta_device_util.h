@@ -83,11 +83,12 @@ __device__ __forceinline__ bf16x8 ds_read_b128_at(uint32_t addr)
 
 // Issue the K-operand reads of one group of 4 MFMA k-steps (A operands of S^T = K Q^T).
 // k_addr[ks] is the lane's LDS address of its chunk for k-step ks in stage 0, row block 0; BASE (a compile-time
-// byte offset, e.g. the stage) goes into the instruction's immediate.
-template <int G, int ROWB, int BASE>
-__device__ __forceinline__ void k_issue(bf16x8 (&ka)[4], const uint32_t (&k_addr)[8])
+// byte offset, e.g. the stage) goes into the instruction's immediate.  GPM: groups per 32-row block (k-steps / 4).
+template <int G, int ROWB, int BASE, int GPM = 2, int KS>
+__device__ __forceinline__ void k_issue(bf16x8 (&ka)[4], const uint32_t (&k_addr)[KS])
 {
-    constexpr int mb = G / 2, ks0 = 4 * (G % 2);
+    static_assert(KS == 4 * GPM, "k-steps per row block");
+    constexpr int mb = G / GPM, ks0 = 4 * (G % GPM);
     static_for<0, 4>([&](auto i) {
         constexpr int ks = ks0 + decltype(i)::value;
         ka[decltype(i)::value] = ds_read_b128_at<BASE + mb * 32 * ROWB>(k_addr[ks]);
@@ -109,6 +110,12 @@ __device__ __forceinline__ void pv_wait(shortx4 (&va)[4][2])
                  : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[1][0]), "+v"(va[1][1]), "+v"(va[2][0]), "+v"(va[2][1]),
                    "+v"(va[3][0]), "+v"(va[3][1])
                  : "n"(PENDING));
+}
+
+template <int PENDING>
+__device__ __forceinline__ void pv_wait(shortx4 (&va)[2][2])
+{
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[1][0]), "+v"(va[1][1]) : "n"(PENDING));
 }
 
 }  // namespace

@@ -82,6 +82,11 @@ def workload(name: str) -> Workload:
         return Workload("C4dense", 1, 24, 128, (30, 48, 80), (6, 8, 8), _uniform(24, (5, 6, 10)), "bf16", 1004)
     if name == "C5":   # per-head windows mixed in one launch
         return Workload("C5", 1, 24, 128, (30, 48, 80), (6, 8, 8), mixed_windows(1005, 24), "bf16", 1005)
+    # Not among the task's configurations: head dimension 64 at sizes that fill the chip, for timing and profiling
+    if name == "D64-2D":    # 128 heads (batch 16 x 8) of the 2D image shape of C2
+        return Workload("D64-2D", 16, 8, 64, (1, 64, 64), (1, 8, 8), _uniform(8, (1, 3, 3)), "bf16", 1006)
+    if name == "D64-3D":    # the grid, tile and window of C4 with the head dimension of C1
+        return Workload("D64-3D", 1, 24, 64, (30, 48, 80), (6, 8, 8), _uniform(24, (3, 3, 3)), "bf16", 1007)
     raise KeyError(name)
 
 

@@ -131,6 +131,11 @@ EDGE_CASES = [
     ("p384-d128-mixed", 2, 3, 128, (6, 16, 24), (6, 8, 8), [(1, 1, 1), (1, 3, 3), (1, 2, 3)]),
     ("single-tile", 1, 1, 64, (6, 8, 8), (6, 8, 8), [(1, 1, 1)]),
     ("p256-d128", 1, 1, 128, (4, 16, 16), (4, 8, 8), [(1, 3, 1)]),
+    # head dimension 64 on each of its DMA-staged shapes: 12 waves (P = 384), 4 waves (P = 256), 2 waves (P = 64, 192)
+    ("p384-d64-mixed", 1, 3, 64, (6, 16, 24), (6, 8, 8), [(1, 1, 1), (1, 3, 3), (1, 2, 3)]),
+    ("p256-d64", 1, 2, 64, (4, 16, 24), (4, 8, 8), [(1, 3, 1), (1, 1, 3)]),
+    ("p64-d64-2d", 2, 2, 64, (1, 32, 40), (1, 8, 8), [(1, 3, 3), (1, 5, 2)]),
+    ("p192-d64", 1, 2, 64, (6, 8, 16), (3, 8, 8), [(3, 1, 1), (1, 1, 3)]),
 ]
 
 
