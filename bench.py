@@ -74,6 +74,10 @@ def parse_args():
     ap.add_argument("--extras", action="store_true",
                     help="instead of the benchmark line, time the entry points built on top of the attention kernel "
                          "(log-denominator output, recall, per-head MSE, mask search) on the workload, one JSON line")
+    ap.add_argument("--mask-demo", action="store_true",
+                    help="instead of the benchmark line, run the general kernel under the STA mask and under the "
+                         "token-granular sliding window of about the same size on the workload's grid (what blocks "
+                         "that are only partly kept cost, Sec. 2.2), one JSON line")
     ap.add_argument("--backward", action="store_true",
                     help="instead of the benchmark line, time the gradient entry point (sta_backward) on the workload, "
                          "one JSON line")
@@ -217,6 +221,10 @@ def cpu_baseline(w, target_seconds):
     }
 
 
+def _uniform(H, wt):
+    return tuple(tuple(wt) for _ in range(H))
+
+
 def window_sweep(layer, w, calls):
     """sta_forward for a list of uniform windows and one per-head mixed table on the layer's grid, dense first."""
     dense_w = tuple(w.tile_grid)
@@ -297,6 +305,31 @@ def main():
             "mean_recall_first_heads": [float(x) for x in mean[:4].cpu()],
             "best_first_heads": [int(x) for x in best[:4].cpu()],
         }))
+        return
+
+    if args.mask_demo:
+        layer.permute_in()
+        wt = w.window_tiles[0]
+        sta_tokens = tuple(wt[a] * w.tile[a] for a in range(3))
+        sw_tokens = tuple(max(x - 1, 1) for x in sta_tokens)            # the odd window just below (17, 23, 23)
+        rows = {}
+        for label, kind, window, census_w in (("sta", sta.STA_MASK_STA, _uniform(w.H, wt), sta_tokens),
+                                              ("sliding_window", sta.STA_MASK_NATTEN, _uniform(w.H, sw_tokens), sw_tokens)):
+            fn = lambda: sta.sta_forward_general(layer.qt, layer.kt, layer.vt, layer.ot, w.grid, w.tile, kind, window)
+            t = spread(event_times_ms(fn, 3, warmup=1))
+            dense_q, mixed_q, totals = sta.sta_block_census(kind, w.grid, w.tile, census_w)
+            blocks = totals[0] + totals[1]
+            rows[label] = {"window_tokens": "x".join(map(str, census_w)), "ms": t["median"],
+                           "dense_blocks_per_head": totals[0], "mixed_blocks_per_head": totals[1],
+                           "us_per_computed_block": t["median"] * 1e3 / (blocks * w.H * w.B),
+                           "matrix_tflops_executed": 4.0 * w.P * w.P * w.D * blocks * w.H * w.B / (t["median"] * 1e-3) / 1e12}
+        fast = spread(event_times_ms(layer.forward, 5))
+        rows["sta_fast_kernel_ms"] = fast["median"]
+        rows["slowdown_sliding_window_vs_sta_same_kernel"] = rows["sliding_window"]["ms"] / rows["sta"]["ms"]
+        rows["what"] = ("general (register-staged) kernel under both masks on %s: B=%d H=%d D=%d grid=%s tile=%s; the sliding "
+                        "window computes every block that any query of the tile touches and evaluates the predicate "
+                        "per score in the mixed ones" % (w.name, w.B, w.H, w.D, w.grid, w.tile))
+        print(json.dumps({"mask_demo": rows}))
         return
 
     bwd = None

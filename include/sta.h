@@ -240,6 +240,23 @@ int sta_block_census(int mask_kind, const int grid[3], const int tile[3],
                      int64_t *mixed_per_q, int64_t totals[3]);
 
 /*
+ * Attention through the library's general (register-staged, untuned) kernel under either mask, for measuring on
+ * one and the same kernel what blocks that are only partly kept cost (Sec. 2.2: dense, mixed and empty blocks;
+ * the Tiled NATTEN line of Table 2).  Not part of the STA path.
+ *   mask_kind = STA_MASK_STA:    window = H*3 window sizes in TILES; same result as sta_forward (to rounding).
+ *   mask_kind = STA_MASK_NATTEN: window = H*3 window sizes in TOKENS; the token-granular sliding window of the
+ *     appendix algorithm "Mask Definition of 3D NATTEN" on the tile-ordered tensors: per axis the window centre
+ *     is the query coordinate clamped into [floor(W/2), L-1-floor(W/2)], kept keys lie within floor(W/2) of it.
+ *     Key tiles no query of the tile keeps are skipped, tiles every query keeps in full run without a mask, the
+ *     others evaluate the predicate per score.  Tiles of at most 1024 tokens.
+ * Tensors, layout, scale, stream and errors as sta_forward.  Supported: D in {64, 128}, P a multiple of 32.
+ */
+int sta_forward_general(const void *q_tiled, const void *k_tiled, const void *v_tiled,
+                        void *o_tiled, int B, int H, int D, const int grid[3],
+                        const int tile[3], int mask_kind, const int *window, float scale,
+                        void *hip_stream);
+
+/*
  * Window in tokens (the paper's notation, e.g. (18,24,24)) -> window in
  * tiles.  STA_ERR_WINDOW unless every entry is a positive multiple of the
  * tile size (Sec. 3.1 assumes W is an integer multiple of T).

@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     sta_kept_flops, sta_key_tile_box, sta_strerror, sta_tile_permute, sta_untile, sta_version,
     sta_window_tokens_to_tiles, sta_workspace_bytes, EXPORTED_SYMBOLS, sta_head_mse_workspace_bytes, sta_head_mse,
     sta_mask_search, sta_attention_recall, sta_block_census, STA_MASK_STA, STA_MASK_NATTEN,
-    sta_backward, sta_backward_workspace_bytes, sta_query_tile_box, sta_head_mse_static,
+    sta_backward, sta_backward_workspace_bytes, sta_query_tile_box, sta_head_mse_static, sta_forward_general,
 )

@@ -18,7 +18,7 @@ _I3 = ctypes.c_int * 3
 EXPORTED_SYMBOLS = (
     "sta_tile_permute", "sta_untile", "sta_forward", "sta_forward_lse", "sta_workspace_bytes", "sta_key_tile_box",
     "sta_dump_key_tiles", "sta_window_tokens_to_tiles", "sta_kept_flops", "sta_strerror", "sta_version",
-    "sta_head_mse_workspace_bytes", "sta_head_mse", "sta_mask_search", "sta_attention_recall", "sta_block_census",
+    "sta_head_mse_workspace_bytes", "sta_head_mse", "sta_mask_search", "sta_attention_recall", "sta_block_census", "sta_forward_general",
     "sta_backward_workspace_bytes", "sta_backward", "sta_query_tile_box", "sta_head_mse_static",
 )
 
@@ -53,6 +53,8 @@ def load_library():
     lib.sta_forward.restype = ci
     lib.sta_forward_lse.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, _I3, _I3, ctypes.POINTER(ci), cf, vp]
     lib.sta_forward_lse.restype = ci
+    lib.sta_forward_general.argtypes = [vp, vp, vp, vp, ci, ci, ci, _I3, _I3, ci, ctypes.POINTER(ci), cf, vp]
+    lib.sta_forward_general.restype = ci
     lib.sta_head_mse_workspace_bytes.argtypes = [ci, ci]
     lib.sta_head_mse_workspace_bytes.restype = ctypes.c_size_t
     lib.sta_head_mse.argtypes = [vp, vp, ci, ci, ci, _I3, vp, ctypes.c_size_t, vp, vp]
@@ -183,6 +185,22 @@ def sta_forward(q_tiled, k_tiled, v_tiled, o_tiled, grid, tile, window_tiles, sc
     _check(lib.sta_forward(_dev(q_tiled, "q"), _dev(k_tiled, "k"), _dev(v_tiled, "v"), _dev(o_tiled, "o"), B, H, D,
                            _i3(grid), _i3(tile), _windows(window_tiles, H), float(scale), ws_ptr, ws_bytes,
                            _stream_ptr(stream)))
+    return o_tiled
+
+
+def sta_forward_general(q_tiled, k_tiled, v_tiled, o_tiled, grid, tile, mask_kind, window, scale=0.0, stream=None):
+    """Attention through the general kernel: mask_kind STA_MASK_STA (window: H entries of (t,h,w) in tiles) or
+    STA_MASK_NATTEN (token-granular sliding window; window: H entries of (t,h,w) in tokens)."""
+    lib = load_library()
+    for t in (q_tiled, k_tiled, v_tiled, o_tiled):
+        if t.dim() != 4 or t.shape != q_tiled.shape or t.dtype != torch.bfloat16:
+            raise ValueError("expect four bf16 [B, H, N, D] tensors of equal shape")
+    B, H, N, D = q_tiled.shape
+    if N != int(grid[0]) * int(grid[1]) * int(grid[2]):
+        raise ValueError("N does not match the grid")
+    _check(lib.sta_forward_general(_dev(q_tiled, "q"), _dev(k_tiled, "k"), _dev(v_tiled, "v"), _dev(o_tiled, "o"), B, H,
+                                   D, _i3(grid), _i3(tile), int(mask_kind), _windows(window, H), float(scale),
+                                   _stream_ptr(stream)))
     return o_tiled
 
 

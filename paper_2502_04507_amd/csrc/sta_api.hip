@@ -552,6 +552,56 @@ int sta_block_census(int mask_kind, const int grid[3], const int tile[3], const 
     return STA_OK;
 }
 
+int sta_forward_general(const void *q_tiled, const void *k_tiled, const void *v_tiled, void *o_tiled, int B, int H, int D,
+                        const int grid[3], const int tile[3], int mask_kind, const int *window, float scale,
+                        void *hip_stream)
+{
+    if (!q_tiled || !k_tiled || !v_tiled || !o_tiled) return STA_ERR_NULL;
+    if (mask_kind != STA_MASK_STA && mask_kind != STA_MASK_NATTEN) return STA_ERR_UNSUPPORTED;
+    Shape s;
+    if (int rc = check_shape(B, H, D, grid, tile, &s)) return rc;
+    if (!window) return STA_ERR_NULL;
+    if (mask_kind == STA_MASK_STA) {
+        if (int rc = check_windows(H, window)) return rc;
+    } else {
+        for (int i = 0; i < 3 * H; ++i)
+            if (window[i] <= 0) return STA_ERR_WINDOW;
+        if (s.P > sta::kMaxTokenWindowTile) return STA_ERR_UNSUPPORTED;
+    }
+    if (!sta::forward_supported((int)s.P, D)) return STA_ERR_UNSUPPORTED;
+    const size_t bytes = (size_t)B * H * s.N * D * 2;
+    if (ranges_overlap(o_tiled, bytes, q_tiled, bytes) || ranges_overlap(o_tiled, bytes, k_tiled, bytes) ||
+        ranges_overlap(o_tiled, bytes, v_tiled, bytes))
+        return STA_ERR_ALIAS;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+    sta::FwdParams p = make_fwd_params(s, H, scale * 1.4426950408889634f);
+    p.T_t = tile[0];
+    p.T_h = tile[1];
+    p.T_w = tile[2];
+    int max_heads = sta::kMaxHeadsPerLaunch;
+    if ((int64_t)B * max_heads > 65535) max_heads = 65535 / B;
+    if (max_heads < 1) return STA_ERR_SHAPE;
+    for (int hb = 0; hb < H; hb += max_heads) {
+        const int heads = (H - hb) < max_heads ? (H - hb) : max_heads;
+        sta::WindowTable win;
+        if (mask_kind == STA_MASK_STA) {
+            fill_window_table(&win, window, hb, heads, s.n);
+        } else {
+            for (int h = 0; h < heads; ++h)
+                for (int a = 0; a < 3; ++a) {
+                    const int w = window[3 * (hb + h) + a], cap = 2 * grid[a];       // 2L already covers the axis from anywhere
+                    win.w[h][a] = (uint16_t)(w < cap ? (w < 65535 ? w : 65535) : (cap < 65535 ? cap : 65535));
+                }
+        }
+        p.head_base = hb;
+        p.heads = heads;
+        if (sta::launch_forward_general(q_tiled, k_tiled, v_tiled, o_tiled, B, D, p, win, mask_kind == STA_MASK_NATTEN,
+                                        static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+            return STA_ERR_HIP;
+    }
+    return STA_OK;
+}
+
 int sta_window_tokens_to_tiles(const int window_tokens[3], const int tile[3], int out_tiles[3])
 {
     if (!window_tokens || !tile || !out_tiles) return STA_ERR_NULL;

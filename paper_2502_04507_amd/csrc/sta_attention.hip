@@ -53,7 +53,35 @@ struct FwdCfg {
     static_assert(KB % 32 == 0 && D % 32 == 0, "MFMA tiling");
 };
 
-template <int D, int NW, int NQ, int KB>
+// Token-granular sliding window (appendix algorithm "Mask Definition of 3D NATTEN") along one axis for a query
+// tile: the window centre of query x is x clamped into [half, L-1-half] (upper clamp first), its keys are the 2*half+1
+// positions around the centre.  c0 / c1: centres of the tile's first / last token (the centre is monotone in x).
+struct TokenWindowAxis {
+    int half, c0, c1;
+    __device__ __forceinline__ void init(int L, int T, int W, int q_tile)
+    {
+        half = (W < 2 * L ? W : 2 * L) / 2;
+        c0 = centre(L, q_tile * T);
+        c1 = centre(L, q_tile * T + T - 1);
+    }
+    __device__ __forceinline__ int centre(int L, int x) const
+    {
+        const int c = x < (L - 1 - half) ? x : (L - 1 - half);
+        return c > half ? c : half;
+    }
+    // key tiles that at least one query of the tile keeps
+    __device__ __forceinline__ StaAxisRange touched(int L, int T) const
+    {
+        const int lo = c0 - half > 0 ? c0 - half : 0, hi = c1 + half < L - 1 ? c1 + half : L - 1;
+        return StaAxisRange{lo / T, hi / T};
+    }
+    // every query of the tile keeps every key of key tile kt
+    __device__ __forceinline__ bool all_kept(int T, int kt) const { return c1 - half <= kt * T && kt * T + T - 1 <= c0 + half; }
+};
+
+// TW: token-granular sliding window instead of the STA mask (win then holds the window in tokens); used to
+// measure what blocks that are only partly kept cost on the same data.
+template <int D, int NW, int NQ, int KB, bool TW = false>
 __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__restrict__ q,
                                                           const bf16_raw *__restrict__ k,
                                                           const bf16_raw *__restrict__ v,
@@ -67,6 +95,8 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
 
     __shared__ __attribute__((aligned(16))) bf16_raw Ks[C::kKElems];
     __shared__ __attribute__((aligned(16))) bf16_raw Vt[C::kVElems];
+    // TW: coordinates of every token of a tile relative to the tile's origin, packed (t << 20 | h << 10 | w)
+    __shared__ __attribute__((aligned(16))) uint32_t intra[TW ? sta::kMaxTokenWindowTile : 4];
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -81,8 +111,35 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
     const size_t bh = (size_t)b * p.H + p.head_base + h_local;
     const uint32_t q_tile = (qblock * C::kQB) / p.P;
 
-    const StaBox box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1],
-                                           win.w[h_local][2], q_tile);
+    StaBox box;
+    TokenWindowAxis ax_t, ax_h, ax_w;
+    // per lane and query block: first kept key coordinate and (kept keys - 1) along each axis
+    int q_lo[NQ][3];
+    uint32_t q_span[3] = {0, 0, 0};
+    if constexpr (TW) {
+        const uint32_t tq_w = q_tile % p.n_w, tq_h = (q_tile / p.n_w) % p.n_h, tq_t = q_tile / (p.n_w * p.n_h);
+        ax_t.init(p.n_t * p.T_t, p.T_t, win.w[h_local][0], tq_t);
+        ax_h.init(p.n_h * p.T_h, p.T_h, win.w[h_local][1], tq_h);
+        ax_w.init(p.n_w * p.T_w, p.T_w, win.w[h_local][2], tq_w);
+        box.t = ax_t.touched(p.n_t * p.T_t, p.T_t);
+        box.h = ax_h.touched(p.n_h * p.T_h, p.T_h);
+        box.w = ax_w.touched(p.n_w * p.T_w, p.T_w);
+        for (uint32_t i = tid; i < p.P; i += C::kThreads) {
+            const uint32_t iw = i % p.T_w, ih = (i / p.T_w) % p.T_h, it = i / (p.T_w * p.T_h);
+            intra[i] = (it << 20) | (ih << 10) | iw;
+        }
+        q_span[0] = 2 * ax_t.half; q_span[1] = 2 * ax_h.half; q_span[2] = 2 * ax_w.half;
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            const uint32_t i = (qblock * C::kQB + wave * NQ * 32 + nq * 32 + lo) % p.P;
+            const uint32_t iw = i % p.T_w, ih = (i / p.T_w) % p.T_h, it = i / (p.T_w * p.T_h);
+            q_lo[nq][0] = ax_t.centre(p.n_t * p.T_t, tq_t * p.T_t + it) - ax_t.half;
+            q_lo[nq][1] = ax_h.centre(p.n_h * p.T_h, tq_h * p.T_h + ih) - ax_h.half;
+            q_lo[nq][2] = ax_w.centre(p.n_w * p.T_w, tq_w * p.T_w + iw) - ax_w.half;
+        }
+    } else {
+        box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1], win.w[h_local][2], q_tile);
+    }
 
     const bf16_raw *qh = q + (bh * p.N + (size_t)qblock * C::kQB + (size_t)wave * NQ * 32) * D;
     const bf16_raw *kh = k + bh * p.N * D;
@@ -153,6 +210,8 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
             for (int e = 0; e < 8; ++e) Vt[(c * 8 + e) * C::kVStride + col] = ve[e];
         }
         __syncthreads();
+        // TW: this sub-block's key tile and position in it, before the walk moves on
+        const int cur_t = it_t, cur_h = it_h, cur_w = it_w, cur_s = it_s;
         advance();
         if (iter + 1 < n_iter) fetch(key_base());   // next sub-block in flight during the math
 
@@ -173,6 +232,32 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
                 for (int nq = 0; nq < NQ; ++nq) S[nq][mb] = mfma_32x32x16(a, Qr[nq][ks], S[nq][mb]);
             }
 
+        // ---- TW: scores of keys outside the query's window become -inf; blocks kept in full skip the test
+        if constexpr (TW) {
+            const bool whole = ax_t.all_kept(p.T_t, cur_t) && ax_h.all_kept(p.T_h, cur_h) && ax_w.all_kept(p.T_w, cur_w);
+            if (!whole) {
+                const int o_t = cur_t * p.T_t, o_h = cur_h * p.T_h, o_w = cur_w * p.T_w;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        // registers 4*g .. 4*g+3  <->  keys 8*g + 4*hb + 0..3 of this 32-key block
+                        const uint4 c4 = *reinterpret_cast<const uint4 *>(&intra[cur_s * KB + mb * 32 + 8 * g + 4 * hb]);
+                        const uint32_t cs[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const int kt = o_t + (int)(cs[t] >> 20), kh_ = o_h + (int)((cs[t] >> 10) & 1023), kw = o_w + (int)(cs[t] & 1023);
+#pragma unroll
+                            for (int nq = 0; nq < NQ; ++nq) {
+                                const bool keep = (uint32_t)(kt - q_lo[nq][0]) <= q_span[0] && (uint32_t)(kh_ - q_lo[nq][1]) <= q_span[1] &&
+                                                  (uint32_t)(kw - q_lo[nq][2]) <= q_span[2];
+                                S[nq][mb][4 * g + t] = keep ? S[nq][mb][4 * g + t] : -INFINITY;
+                            }
+                        }
+                    }
+            }
+        }
+
         // ---- online softmax (one query column per lane) -------------------------
         bf16x8 Pb[NQ][MB][2];
 #pragma unroll
@@ -184,8 +269,10 @@ __global__ __launch_bounds__(NW * 64) void sta_fwd_kernel(const bf16_raw *__rest
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[nq][mb][r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             const float m_new = fmaxf(m_run[nq], mx);
-            const float alpha = exp2f((m_run[nq] - m_new) * p.scale_log2e);
-            const float mneg = -m_new * p.scale_log2e;
+            // TW: a query may have met masked keys only so far; the offset then stays at 0 so that no inf - inf appears
+            const float m_off = (TW && m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = exp2f((m_run[nq] - m_off) * p.scale_log2e);
+            const float mneg = -m_off * p.scale_log2e;
             m_run[nq] = m_new;
             float psum = 0.f;
 #pragma unroll
@@ -808,27 +895,27 @@ __global__ void sta_dump_key_tiles_kernel(sta::FwdParams p, sta::WindowTable win
     for (; c < p.n_tiles; ++c) out[c] = -1;
 }
 
-template <int D, int NW, int NQ, int KB>
+template <int D, int NW, int NQ, int KB, bool TW = false>
 hipError_t launch_cfg(const void *q, const void *k, const void *v, void *o, int B, const sta::FwdParams &p,
                       const sta::WindowTable &win, hipStream_t stream)
 {
     using C = FwdCfg<D, NW, NQ, KB>;
     dim3 grid(p.N / C::kQB, (uint32_t)B * p.heads);
     dim3 block(C::kThreads);
-    sta_fwd_kernel<D, NW, NQ, KB><<<grid, block, 0, stream>>>(
+    sta_fwd_kernel<D, NW, NQ, KB, TW><<<grid, block, 0, stream>>>(
         static_cast<const bf16_raw *>(q), static_cast<const bf16_raw *>(k), static_cast<const bf16_raw *>(v),
         static_cast<bf16_raw *>(o), p, win);
     return hipGetLastError();
 }
 
-template <int D>
+template <int D, bool TW = false>
 hipError_t launch_d(const void *q, const void *k, const void *v, void *o, int B, const sta::FwdParams &p,
                     const sta::WindowTable &win, hipStream_t stream)
 {
     const uint32_t P = p.P;
-    if (P % 128 == 0) return launch_cfg<D, 4, 1, 64>(q, k, v, o, B, p, win, stream);
-    if (P % 64 == 0) return launch_cfg<D, 2, 1, 64>(q, k, v, o, B, p, win, stream);
-    if (P % 32 == 0) return launch_cfg<D, 1, 1, 32>(q, k, v, o, B, p, win, stream);
+    if (P % 128 == 0) return launch_cfg<D, 4, 1, 64, TW>(q, k, v, o, B, p, win, stream);
+    if (P % 64 == 0) return launch_cfg<D, 2, 1, 64, TW>(q, k, v, o, B, p, win, stream);
+    if (P % 32 == 0) return launch_cfg<D, 1, 1, 32, TW>(q, k, v, o, B, p, win, stream);
     return hipErrorInvalidValue;
 }
 
@@ -876,6 +963,17 @@ hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, 
     if (p.P % 128 == 0 && !sta::g_force_generic)
         return launch_fast<128, 4, 32, 2, 3>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
     return launch_d<128>(q, k, v, o, B, p, win, stream);
+}
+
+hipError_t launch_forward_general(const void *q, const void *k, const void *v, void *o, int B, int D, const FwdParams &p,
+                                  const WindowTable &win, bool token_window, hipStream_t stream)
+{
+    if (!forward_supported((int)p.P, D)) return hipErrorInvalidValue;
+    if (token_window) {
+        if (p.P > kMaxTokenWindowTile || p.T_t > 1023 || p.T_h > 1023 || p.T_w > 1023) return hipErrorInvalidValue;
+        return D == 64 ? launch_d<64, true>(q, k, v, o, B, p, win, stream) : launch_d<128, true>(q, k, v, o, B, p, win, stream);
+    }
+    return D == 64 ? launch_d<64>(q, k, v, o, B, p, win, stream) : launch_d<128>(q, k, v, o, B, p, win, stream);
 }
 
 hipError_t launch_dump_key_tiles(const FwdParams &p, const WindowTable &win, int32_t *counts, int32_t *lists,

@@ -46,6 +46,7 @@ struct FwdParams {
     uint32_t head_base;    // first head of this launch
     uint32_t heads;        // heads in this launch
     float scale_log2e;     // softmax scale * log2(e)
+    uint32_t T_t = 1, T_h = 1, T_w = 1;   // tile shape in tokens (used by the token-masked sliding-window kernel only)
     float *lse = nullptr;  // optional output [B,H,N] (tiled order): ln of each row's softmax denominator; may be null
     // work splitting below one query block (filled in by the launcher): item ids from split_first on are run
     // by split_parts workgroups each, which leave partial results in split_ws
@@ -60,6 +61,11 @@ hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, 
                           const FwdParams &p, const WindowTable &win, const HeadOrder &order, float *split_ws,
                           size_t split_ws_floats, hipStream_t stream);
 size_t forward_split_workspace_bytes(int P, int D);    // upper bound of what the splitting ever uses
+// The general (register-staged) kernel for any supported shape.  token_window = false: the STA mask, win in tiles
+// (same results as launch_forward).  token_window = true: the token-granular sliding window, win in tokens.
+hipError_t launch_forward_general(const void *q, const void *k, const void *v, void *o, int B, int D, const FwdParams &p,
+                                  const WindowTable &win, bool token_window, hipStream_t stream);
+constexpr uint32_t kMaxTokenWindowTile = 1024;         // tokens per tile the sliding-window kernel's table holds
 bool forward_supported(int P, int D);
 extern bool g_force_generic;   // debugging aid: route every shape through the generic kernel
 

@@ -166,3 +166,72 @@ def test_mask_search_parity():
         if srt[1] > 1.10 * srt[0]:
             assert bg[h] == ref_b2[h], (h, ref_l2[:, h], losses2[:, h].cpu().numpy())
         assert bg[h] != 3                                    # the duplicate at the end never replaces the first
+
+
+# ---- the token-granular sliding window through the general kernel (block taxonomy of Sec. 2.2 made measurable) ----
+
+def _general(w, qt, kt, vt, mask_kind, window):
+    ot = torch.full_like(qt, float("nan"))
+    sta.sta_forward_general(qt, kt, vt, ot, w.grid, w.tile, mask_kind, window)
+    o = torch.full_like(ot, float("nan"))
+    sta.sta_untile(ot, o, w.grid, w.tile)
+    torch.cuda.synchronize()
+    return o.cpu()
+
+
+@pytest.mark.parametrize("name,D,grid,tile,windows_tokens", [
+    # 32-token tiles, odd windows, borders on every axis
+    ("sw-p32-d64", 64, (6, 16, 16), (2, 4, 4), [(3, 5, 7), (5, 3, 3)]),
+    # 128-token tiles; an even entry (floor half), an entry longer than its axis, a one-token entry
+    ("sw-p128-d128", 128, (4, 16, 24), (2, 8, 8), [(3, 9, 11), (1, 6, 49)]),
+    # 2D image, 64-token tiles
+    ("sw-p64-d64-2d", 64, (1, 32, 40), (1, 8, 8), [(1, 7, 7), (1, 33, 5)]),
+    # the paper's 6x8x8 tile
+    ("sw-p384-d128", 128, (6, 16, 24), (6, 8, 8), [(5, 11, 11)]),
+])
+def test_sliding_window_parity(name, D, grid, tile, windows_tokens):
+    """The sliding-window predicate is the STA predicate at tile (1,1,1) (pinned on the CPU), so the oracle for the
+    token-masked run is the oracle's attention with unit tiles on the same raster tensors."""
+    H = len(windows_tokens)
+    w = syn.custom(name, 1, H, D, grid, tile, [(1, 1, 1)] * H, "bf16", seed=9090)
+    q, k, v = syn.make_qkv(w)
+    qt, kt, vt = _tiled_inputs(w, q, k, v)
+    out = _general(w, qt, kt, vt, sta.STA_MASK_NATTEN, windows_tokens).float().numpy()
+    for h in range(H):
+        ref = orc.attention(q[0, h].float().numpy(), k[0, h].float().numpy(), v[0, h].float().numpy(), grid, (1, 1, 1),
+                            windows_tokens[h])
+        print(name, h, gu.assert_parity(out[0, h], ref, "%s h%d" % (name, h)))
+
+
+def test_sliding_window_of_one_token_returns_v():
+    """Window 1x1x1 in tokens: every query keeps only its own position, the softmax has one term, O = V exactly."""
+    w = syn.custom("sw-self", 1, 2, 64, (4, 8, 16), (2, 8, 8), [(1, 1, 1)] * 2, "bf16", seed=9091)
+    q, k, v = syn.make_qkv(w)
+    qt, kt, vt = _tiled_inputs(w, q, k, v)
+    out = _general(w, qt, kt, vt, sta.STA_MASK_NATTEN, [(1, 1, 1)] * 2)
+    assert torch.equal(out.view(torch.int16), v.view(torch.int16))
+
+
+def test_general_kernel_with_sta_mask_matches_oracle_and_fast_path():
+    w = syn.custom("gen-sta", 1, 2, 128, (6, 16, 24), (6, 8, 8), [(1, 3, 3), (1, 1, 2)], "bf16", seed=9092)
+    q, k, v = syn.make_qkv(w)
+    qt, kt, vt = _tiled_inputs(w, q, k, v)
+    out = _general(w, qt, kt, vt, sta.STA_MASK_STA, w.window_tiles).float().numpy()
+    fast = gu.gpu_chain(w, q, k, v).float().numpy()
+    for h in range(w.H):
+        gu.assert_parity(out[0, h], gu.oracle_rows(w, q, k, v, 0, h, None), "gen-sta h%d" % h)
+    assert np.abs(out - fast).max() <= 2.0 ** -6 * np.abs(fast).max()
+
+
+def test_sliding_window_errors():
+    t = lambda: torch.zeros((1, 1, 64, 64), dtype=torch.bfloat16, device=DEV)
+    a, b, c, d = t(), t(), t(), t()
+    with pytest.raises(sta.StaError) as e:          # unknown mask
+        sta.sta_forward_general(a, b, c, d, (1, 8, 8), (1, 8, 8), 7, [(1, 3, 3)])
+    assert e.value.status == 4
+    with pytest.raises(sta.StaError) as e:          # non-positive window
+        sta.sta_forward_general(a, b, c, d, (1, 8, 8), (1, 8, 8), sta.STA_MASK_NATTEN, [(1, 0, 3)])
+    assert e.value.status == 3
+    with pytest.raises(sta.StaError) as e:          # output aliases an input
+        sta.sta_forward_general(a, b, c, a, (1, 8, 8), (1, 8, 8), sta.STA_MASK_NATTEN, [(1, 3, 3)])
+    assert e.value.status == 5
