@@ -923,13 +923,12 @@ hipError_t launch_d(const void *q, const void *k, const void *v, void *o, int B,
 
 namespace sta {
 
-bool g_force_generic = false;
 
 bool forward_supported(int P, int D) { return (D == 64 || D == 128) && P > 0 && P % 32 == 0; }
 
 size_t forward_split_workspace_bytes(int P, int D)
 {
-    if (D != 128 || P % 128 != 0 || g_force_generic) return 0;
+    if (D != 128 || P % 128 != 0) return 0;
     // About one resident set of workgroups leaves partial results, QB queries x (128 + 2) floats each; twice
     // that, because ids that name no item (ranges of unequal length) also take a slot.
     if (P % 384 == 0) return (size_t)2 * resident_workgroups(1) * 384 * 130 * sizeof(float);
@@ -947,20 +946,18 @@ hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, 
         // kernel 459.  64-token tiles (2D images) get 2-wave workgroups: 575 TFLOP/s on 128 heads of a 64x64 image
         // (32-key sub-blocks, 2 stages; 64-key sub-blocks 501, 3 stages 537; general kernel 237).  That shape moves
         // 147 KB of K and V from L2 per 9.4 MFLOP work item, about 9 TB/s at this rate: it is bound by L2, not MFMA.
-        if (!sta::g_force_generic) {
-            if (p.P % 384 == 0) return launch_fast<64, 12, 64, 2, 1>(q, k, v, o, B, p, win, order, nullptr, 0, stream);
-            if (p.P % 128 == 0) return launch_fast<64, 4, 64, 2, 3>(q, k, v, o, B, p, win, order, nullptr, 0, stream);
-            if (p.P % 64 == 0) return launch_fast<64, 2, 32, 2, 3>(q, k, v, o, B, p, win, order, nullptr, 0, stream);
-        }
+        if (p.P % 384 == 0) return launch_fast<64, 12, 64, 2, 1>(q, k, v, o, B, p, win, order, nullptr, 0, stream);
+        if (p.P % 128 == 0) return launch_fast<64, 4, 64, 2, 3>(q, k, v, o, B, p, win, order, nullptr, 0, stream);
+        if (p.P % 64 == 0) return launch_fast<64, 2, 32, 2, 3>(q, k, v, o, B, p, win, order, nullptr, 0, stream);
         return launch_d<64>(q, k, v, o, B, p, win, stream);
     }
     // A tile of 384 tokens (the paper's 6x8x8) gets one 12-wave workgroup per query tile: every K/V sub-block
     // fetched from L2 then serves 384 queries instead of 128.  Measured at the 115,200-token layer, window
     // 3x3x3: 12.8-13.1 ms against 13.6-13.7 ms for the 4-wave shape in the same session; 2 LDS stages were
     // faster than 3 (13.15 ms) or 4 (13.3 ms).
-    if (p.P % 384 == 0 && !sta::g_force_generic)
+    if (p.P % 384 == 0)
         return launch_fast<128, 12, 32, 2, 1>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
-    if (p.P % 128 == 0 && !sta::g_force_generic)
+    if (p.P % 128 == 0)
         return launch_fast<128, 4, 32, 2, 3>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
     return launch_d<128>(q, k, v, o, B, p, win, stream);
 }

@@ -394,7 +394,9 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
     constexpr int OPS = 2, STAGE_B = OPS * kTileB;
     constexpr int Q_TILE = 0, G_TILE = kTileB;
     constexpr int P_XCHG = 2 * STAGE_B;                 // 4 column blocks x 2 planes x 64 lanes x 16 B
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 4 * 2048];
+    constexpr int STATS = P_XCHG + 4 * 2048;            // per stage: lse then delta of the 32 staged query rows
+    constexpr int STAT_B = 2 * kSub * 4;
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 4 * 2048 + 2 * STAT_B];
 
     uint32_t kblock, bh_rank;
     if (!work_item(chunk, p.N / kCols, n_bh, &kblock, &bh_rank)) return;
@@ -418,10 +420,11 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
     // DMA: each operand is 8 instructions of 1 KB (4 rows); wave w issues instruction w of each.
     const int dma_row = 4 * wave + (lane >> 4);
     const uint32_t src_off = src_chunk_offset(dma_row, lane & 15);
-    // Row statistics of the sub-block being fetched (lse for the first role, delta for the second): rows
-    // 8*g + 4*hb + t of it, one float4 per g.
-    const float *stat = probs_role ? lse : delta;
-    floatx4 stat_next[4];
+    // Row statistics of the staged sub-block (lse for the first role, delta for the second) travel with it: one
+    // 4-byte-per-lane DMA instruction of the last wave brings the 32 + 32 floats into LDS, and every wave reads the
+    // rows 8*g + 4*hb + t its accumulator registers belong to from there.  (Loading them from global memory into
+    // registers in every wave, 32 wide loads per sub-block and CU, cost 2 ms of the launch.)
+    const float *stat_src = (lane < kSub ? lse : delta) + head_row + (lane & (kSub - 1));
     auto issue_loads = [&](int stage, uint32_t first_row) {
         const size_t base = (size_t)first_row * kRowB;
         char *dst = smem + stage * STAGE_B + wave * 1024;
@@ -429,9 +432,9 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
                                          STA_LDS_PTR(dst + Q_TILE), 16, 0, 0);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + src_off),
                                          STA_LDS_PTR(dst + G_TILE), 16, 0, 0);
-        const size_t at = head_row + first_row + 4 * hb;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) stat_next[g] = *reinterpret_cast<const floatx4 *>(stat + at + 8 * g);
+        if (wave == 7)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(stat_src + first_row),
+                                             STA_LDS_PTR(smem + STATS + stage * STAT_B), 4, 0, 0);
     };
 
     const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
@@ -465,13 +468,18 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
     auto sub_block = [&](auto stage_c) {
         constexpr int ST = decltype(stage_c)::value * STAGE_B;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        float st[16];
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) st[4 * g + t] = stat_next[g][t];
         __syncthreads();       // the stage is complete; the other stage and the exchange buffer are free
         issue_next();
+        float st[16];
+        {
+            const char *stats = smem + STATS + decltype(stage_c)::value * STAT_B + (probs_role ? 0 : kSub * 4) + 16 * hb;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const floatx4 x = *reinterpret_cast<const floatx4 *>(stats + 32 * g);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) st[4 * g + t] = x[t];
+            }
+        }
         floatx16 X;
         if (probs_role) {
             X = rows_times_resident<ST + Q_TILE>(row_addr, resident);           // S = Q K^T (queries x keys)
@@ -791,7 +799,7 @@ hipError_t launch_backward(const void *q, const void *k, const void *v, const vo
     const bf16_raw *vv = static_cast<const bf16_raw *>(v), *gg = static_cast<const bf16_raw *>(d_o);
     if (D == 64)
         return launch_backward_generic<64>(qq, kk, vv, o, d_o, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream);
-    if (p.P % kCols != 0 || g_force_generic)
+    if (p.P % kCols != 0)
         return launch_backward_generic<128>(qq, kk, vv, o, d_o, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream);
     if (compute_delta) {
         const size_t rows = (size_t)B * p.H * p.N;   // all heads of the tensor at once

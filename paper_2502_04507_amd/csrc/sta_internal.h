@@ -67,7 +67,6 @@ hipError_t launch_forward_general(const void *q, const void *k, const void *v, v
                                   const WindowTable &win, bool token_window, hipStream_t stream);
 constexpr uint32_t kMaxTokenWindowTile = 1024;         // tokens per tile the sliding-window kernel's table holds
 bool forward_supported(int P, int D);
-extern bool g_force_generic;   // debugging aid: route every shape through the generic kernel
 
 // ---- gradients ---------------------------------------------------------------
 // delta: float [B, H, N] scratch (dO_i . O_i per query row), filled by the call when compute_delta is set.
