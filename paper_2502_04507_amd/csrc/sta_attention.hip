@@ -403,9 +403,10 @@ __host__ __device__ __forceinline__ size_t split_part_floats(int QB) { return (s
 //   D = 64 (two rows span the banks):    K: c ^ ((r >> 1) & 7)      V: c ^ (((r >> 1) & 1) << 2)
 // (16 lanes of a b128 read take rows r..r+15 at one logical chunk: they must land on 16 different 16-byte bank
 // groups; 32 lanes of a transposing read take 4 rows x 4 consecutive chunks: likewise.)
-// Instances in use: <12, 32, 2, 1> (384-token tiles: one 12-wave workgroup per query tile and per CU) and
-// <4, 32, 2, 3> (other tile sizes that are multiples of 128: three 4-wave workgroups per CU; 32-key sub-blocks
-// measured 3-5 % faster than 64-key ones in this shape).
+// Instances in use (<D, NW, KB, STAGES, MINB>), chosen in launch_forward: D = 128: <128, 12, 32, 2, 1> for 384-token
+// tiles (one 12-wave workgroup per query tile and per CU) and <128, 4, 32, 2, 3> for other multiples of 128 (three
+// 4-wave workgroups per CU; 32-key sub-blocks measured 3-5 % faster than 64-key ones in this shape); D = 64:
+// <64, 12, 64, 2, 1>, <64, 4, 64, 2, 3> and, for other multiples of 64 tokens, <64, 2, 32, 2, 3>.
 // ---------------------------------------------------------------------------
 template <int D>
 __device__ __forceinline__ constexpr int k_swizzle(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }

@@ -37,7 +37,8 @@ def _gpu_lse(w, qt, kt, vt, windows):
 @pytest.mark.parametrize("name,B,H,D,grid,tile,windows", [
     ("lse-p384", 1, 2, 128, (6, 16, 24), (6, 8, 8), [(1, 3, 3), (1, 1, 2)]),      # 12-wave kernel
     ("lse-p128", 2, 2, 128, (2, 16, 16), (2, 8, 8), [(1, 2, 1), (1, 9, 9)]),      # 4-wave kernel
-    ("lse-d64", 1, 2, 64, (2, 8, 16), (1, 8, 8), [(1, 1, 3), (3, 1, 1)]),         # generic kernel
+    ("lse-d64", 1, 2, 64, (2, 8, 16), (1, 8, 8), [(1, 1, 3), (3, 1, 1)]),         # 2-wave kernel, head dimension 64
+    ("lse-p32", 1, 2, 64, (4, 8, 8), (2, 4, 4), [(1, 3, 1), (3, 1, 3)]),          # general kernel
 ])
 def test_lse_parity(name, B, H, D, grid, tile, windows):
     w = syn.custom(name, B, H, D, grid, tile, windows, "bf16", seed=901)

@@ -273,7 +273,9 @@ def test_full_window_equals_dense_attention_on_gpu():
 
 
 @pytest.mark.parametrize("D,grid,tile,workspace", [
-    (64, (12, 24, 32), (6, 8, 8), False),          # generic kernel, ascending walk
+    (64, (4, 16, 16), (2, 4, 4), False),           # general kernel (32-token tiles), ascending walk
+    (64, (12, 24, 32), (6, 8, 8), False),          # 12-wave kernel at head dimension 64
+    (64, (1, 40, 48), (1, 8, 8), False),           # 2-wave kernel (64-token tiles), 30 tiles
     (128, (12, 24, 32), (6, 8, 8), False),         # 12-wave kernel: residue-order walk of the box
     (128, (12, 24, 32), (6, 8, 8), True),          # ... with items split along the keys
     (128, (4, 24, 32), (2, 8, 8), False),          # 4-wave kernel
@@ -374,7 +376,8 @@ def test_attention_parity_c4_dense_sampled():
 
 
 def test_many_batch_entries_take_the_head_chunk_limit():
-    """B = 300: the number of heads per launch is cut to 65535 / B, the limit of the generic kernel's grid."""
+    """B = 300: the number of heads per launch is cut to 65535 / B (the limit of the general kernel's grid, applied
+    to every kernel), so the two heads go out in separate launches."""
     w = syn.custom("manybatch", 300, 2, 64, (1, 8, 16), (1, 8, 8), [(1, 1, 1), (1, 1, 3)], "bf16", seed=77)
     q, k, v = syn.make_qkv(w)
     out = gu.gpu_chain(w, q, k, v).float().numpy()
