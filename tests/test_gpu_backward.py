@@ -222,3 +222,34 @@ def test_backward_errors():
         sta.sta_backward(*a[:5], torch.zeros((1, 1, 48), dtype=torch.float32, device=DEV), *a[5:], (1, 6, 8), (1, 6, 8),
                          [(1, 1, 1)], ws)
     assert e.value.status == 4
+
+
+def _random_grad_shapes(n_cases, seed):
+    rng = np.random.default_rng(seed)
+    tiles = [(6, 8, 8), (2, 8, 8), (1, 8, 8), (4, 4, 8), (2, 4, 4), (3, 8, 8), (2, 6, 8)]
+    cases = []
+    while len(cases) < n_cases:
+        tile = tiles[rng.integers(len(tiles))]
+        n = tuple(int(rng.integers(1, 4)) for _ in range(3))
+        grid = tuple(n[a] * tile[a] for a in range(3))
+        if grid[0] * grid[1] * grid[2] > 2400:
+            continue
+        D = int(rng.choice([64, 128]))
+        H = int(rng.integers(1, 3))
+        windows = [tuple(int(rng.integers(1, 2 * n[a] + 2)) for a in range(3)) for _ in range(H)]
+        cases.append((H, D, grid, tile, windows))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_grad_shapes(12, seed=20250208),
+                         ids=lambda c: "H%d-D%d-g%s-t%s" % (c[0], c[1], "x".join(map(str, c[2])), "x".join(map(str, c[3]))))
+def test_backward_parity_seeded_shape_sweep(case):
+    H, D, grid, tile, windows = case
+    w = syn.custom("bwd-sweep", 1, H, D, grid, tile, windows, "bf16", seed=hash((grid, tile, D)) % 100000)
+    q, k, v = syn.make_qkv(w)
+    g = syn.make_dout(w)
+    (dq, dk, dv), _ = gpu_backward(w, q, k, v, g)
+    for h in range(H):
+        rq, rk, rv = oracle_backward(w, q, k, v, g, 0, h)
+        for label, got, ref in (("dQ", dq, rq), ("dK", dk, rk), ("dV", dv, rv)):
+            assert_grad_parity(got[0, h].float().numpy(), ref, "sweep %s %s h%d" % (case, label, h))

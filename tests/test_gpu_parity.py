@@ -406,3 +406,38 @@ def test_errors_with_device_buffers():
         sta.sta_forward(x, x, x, y, (1, 8, 8), (1, 4, 4), [(1, 1, 1)])      # P = 16
     assert e.value.status == 4
     torch.cuda.synchronize()
+
+
+# --------------------------------------------------------------------------
+# A seeded sweep over shapes: every kernel instance, borders, windows of all kinds
+# --------------------------------------------------------------------------
+def _random_shapes(n_cases, seed):
+    rng = np.random.default_rng(seed)
+    tiles = [(6, 8, 8), (2, 8, 8), (1, 8, 8), (4, 4, 8), (2, 4, 4), (3, 8, 8), (1, 4, 8), (2, 6, 8)]
+    cases = []
+    while len(cases) < n_cases:
+        tile = tiles[rng.integers(len(tiles))]
+        n = tuple(int(rng.integers(1, 5)) for _ in range(3))
+        grid = tuple(n[a] * tile[a] for a in range(3))
+        N = grid[0] * grid[1] * grid[2]
+        if N > 4608 or (tile[0] * tile[1] * tile[2]) % 32 != 0:
+            continue
+        D = int(rng.choice([64, 128]))
+        H = int(rng.integers(1, 4))
+        B = int(rng.integers(1, 3))
+        windows = [tuple(int(rng.integers(1, 2 * n[a] + 2)) for a in range(3)) for _ in range(H)]
+        cases.append((B, H, D, grid, tile, windows))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_shapes(24, seed=20250207), ids=lambda c: "B%d-H%d-D%d-g%s-t%s" % (c[0], c[1], c[2], "x".join(map(str, c[3])), "x".join(map(str, c[4]))))
+def test_attention_parity_seeded_shape_sweep(case):
+    B, H, D, grid, tile, windows = case
+    w = syn.custom("sweep", B, H, D, grid, tile, windows, "bf16", seed=hash((grid, tile, D)) % 100000)
+    q, k, v = syn.make_qkv(w)
+    for workspace in (False, True):
+        out = gu.gpu_chain(w, q, k, v, workspace=workspace).float().numpy()
+        assert np.isfinite(out).all()
+        for b in range(B):
+            for h in range(H):
+                gu.assert_parity(out[b, h], gu.oracle_rows(w, q, k, v, b, h, None), "sweep %s b%d h%d" % (case, b, h))
