@@ -740,7 +740,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_
                 *reinterpret_cast<floatx4 *>(wo + db * 32 + g * 8 + hb * 4) = ov;
             }
         if (hb == 0) {
-            ws[(size_t)QB * D + wave * 32 + lo] = m_run;
+            ws[(size_t)QB * D + wave * 32 + lo] = m_run * c;      // the merge takes base-2 units
             ws[(size_t)QB * D + QB + wave * 32 + lo] = l_tot;
         }
         return;
@@ -776,8 +776,452 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_
     }
 }
 
+// The same kernel built on v_mfma_f32_16x16x32_bf16 (head dimension 128, 32-key sub-blocks).  On this chip the run
+// time on real data follows the energy of the instruction stream (the package sits at its power limit and lowers
+// the clock), and the 16x16x32 shape is the cheaper one per flop: it reads and writes 4 accumulator registers per
+// 16 Kflop where 32x32x16 moves 16 per 32 Kflop.  Measured with nothing but matrix instructions on N(0,1) operands,
+// two waves per SIMD: 2019 TFLOP/s against 1784 (equal, 2440, on constant operands).
+// Layout: a lane holds column c16 = lane & 15 of a 16x16 result (a query) and rows 4*g4 .. 4*g4+3 (g4 = lane >> 4);
+// of an operand it holds row/column c16 and the k-chunk 8*g4 .. 8*g4+7.  A wave's 32 queries are two query blocks;
+// every K and V fragment read from LDS feeds both.  One swizzle serves the row reads of K and the transposing reads
+// of V: 16-byte chunk c of row r sits at position c ^ swizzle16(r), swizzle16(r) = 2 * (r & 7).  Why this one (all
+// rows start at bank 0, a row being 256 bytes = the 64 banks):
+//  - a transposing 8-byte read is served 32 lanes at a time; those lanes read 8 consecutive rows, two neighbouring
+//    chunks (2*cb, 2*cb + 1) of each: the rows' swizzles must differ above bit 0;
+//  - a 16-byte read is served 16 lanes at a time, and measured with the bank-conflict counter those 16 are not
+//    consecutive lanes but lanes 0-7 together with lanes 24-31 (then 8-15 with 16-23, and the same in the upper
+//    half): rows 0..7 at chunk x and rows 8..15 at chunk x ^ 1.  The two sets of positions x ^ swizzle16(0..7) and
+//    x ^ 1 ^ swizzle16(8..15) are the even and the odd ones: disjoint.
+// (The bijective 4-bit swizzles that look right for 16 consecutive lanes cost a 2-way conflict on every K read.)
+__device__ __forceinline__ constexpr int swizzle16(int r) { return (r & 7) << 1; }
+
+template <int NW, int STAGES, int MINB, bool PRESCALE>
+__global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_raw *__restrict__ q,
+                                                                 const bf16_raw *__restrict__ k,
+                                                                 const bf16_raw *__restrict__ v,
+                                                                 bf16_raw *__restrict__ o, sta::FwdParams p,
+                                                                 sta::WindowTable win, sta::HeadOrder order,
+                                                                 uint32_t n_bh)
+{
+    constexpr int D = 128, KB = 32;
+    constexpr int QB = NW * 32;                    // queries per workgroup: one 32-query block per wave
+    constexpr int KS = D / 32;                     // k-steps of 32 channels in S^T = K Q^T
+    constexpr int CB = D / 16;                     // 16-channel blocks of O^T
+    constexpr int ROWB = D * 2;                    // bytes per key row in LDS
+    constexpr int TILE_BYTES = KB * ROWB;          // one K (or V) sub-block
+    constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // K then V
+    constexpr int INSTR = TILE_BYTES / 1024;       // 1 KB DMA instructions per operand per sub-block
+    constexpr int WANT_LOADERS = NW < 4 ? NW : (NW < 8 ? 4 : 8);
+    constexpr int LOADERS = WANT_LOADERS < INSTR ? WANT_LOADERS : INSTR;     // waves 0 .. LOADERS-1 issue the DMA
+    constexpr int LOADS = INSTR / LOADERS;         // ... this many instructions per operand each
+    constexpr int RPI = 1024 / ROWB;               // key rows per DMA instruction (4 or 8)
+    constexpr int IPB = 16 / RPI;                  // DMA instructions per block of 16 rows
+    constexpr int LPR = ROWB / 16;                 // lanes (16-byte chunks) per row
+    static_assert(KB % 32 == 0 && INSTR % LOADERS == 0 && LOADS >= 1 && LOADERS <= NW && LOADERS % IPB == 0,
+                  "sub-block shape");
+    static_assert(STAGES == 2, "LDS stages");
+
+    // the K/V stages; at the end every wave passes its 32 output rows (32 * ROWB bytes) through the same memory
+    constexpr int OUT_BYTES = QB * ROWB;
+    __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_BYTES > OUT_BYTES ? STAGES * STAGE_BYTES : OUT_BYTES];
+
+    // ---- work item (see fwd_item_of), possibly one part of a split item
+    uint32_t item_id = blockIdx.x, part = 0;
+    const bool is_part = blockIdx.x >= p.split_first;
+    if (is_part) {
+        const uint32_t idx = blockIdx.x - p.split_first;
+        item_id = p.split_first + idx / p.split_parts;
+        part = idx - (item_id - p.split_first) * p.split_parts;
+    }
+    const FwdItem item = fwd_item_of<QB>(item_id, p, order, n_bh);
+    if (!item.valid) return;
+    const uint32_t qblock = item.qblock, h_local = item.h_local;
+    const size_t bh = item.bh;
+    const uint32_t q_tile = (qblock * QB) / p.P;
+    const StaBox box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1],
+                                           win.w[h_local][2], q_tile);
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int c16 = lane & 15;                     // column of a 16x16 result this lane holds (a query)
+    const int g4 = lane >> 4;                      // its rows 4*g4 .. 4*g4+3; k-chunk 8*g4 .. 8*g4+7 of an operand
+
+    const bf16_raw *qh = q + (bh * p.N + (size_t)qblock * QB + (size_t)wave * 32) * D;
+    const char *kh = reinterpret_cast<const char *>(k + bh * p.N * D);
+    const char *vh = reinterpret_cast<const char *>(v + bh * p.N * D);
+
+    // ---- DMA loads.  Each wave-wide 16 B/lane instruction fills 1 KB of LDS = RPI consecutive key rows (a
+    // lane's LDS slot is fixed by the hardware: base + 16*lane), so the swizzle is applied on the global side: the
+    // lane fetches the logical chunk that belongs at its slot.  The KB keys of a sub-block are taken as blocks of
+    // 16 rows; loading wave w fetches rows RPI*(w%IPB) .. +RPI-1 of the blocks LOADS*(w/IPB) .. +LOADS-1, one
+    // instruction per block.  Both swizzles depend on the row only through row & 15, so a lane's offset inside
+    // its block is the same for all its instructions and the rest of the address is wave-uniform: one 32-bit
+    // lane offset per operand on top of a scalar base, and no vector arithmetic per load.
+    uint32_t kv_lane_off;                           // K and V share one swizzle here
+    {
+        const int lrow = RPI * (wave % IPB) + lane / LPR;   // row & 15 of every row this lane fetches
+        const int slot = lane % LPR;
+        kv_lane_off = (uint32_t)(lrow * ROWB + ((slot ^ swizzle16(lrow)) << 4));
+    }
+    auto issue_loads = [&](int stage, size_t key_byte_base) {
+        char *sdst = smem + stage * STAGE_BYTES;                           // only waves < LOADERS get here
+        uint32_t koff = kv_lane_off;
+        asm volatile("" : "+v"(koff));                  // keep the lane offset 32-bit next to a scalar base
+        const uint32_t voff = koff;
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int block16 = LOADS * (wave / IPB) + i;
+            const size_t gbase = key_byte_base + (size_t)block16 * (16 * ROWB);
+            char *kdst = sdst + (16 * block16 + RPI * (wave % IPB)) * ROWB;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + gbase + koff),
+                                             STA_LDS_PTR(kdst), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + gbase + voff),
+                                             STA_LDS_PTR(kdst + TILE_BYTES), 16, 0, 0);
+        }
+    };
+
+    // ---- per-lane constants of the operand reads
+    // K (A operand of S^T = K Q^T, 16 keys x 32 channels): key row 16*kb + c16, logical chunk 4*ks + g4
+    // The addresses of the other k-steps / channel blocks differ from the first one's only in bits that the
+    // swizzle XORs, so they are formed from one base per operand with one XOR each where they are used, which costs
+    // a few vector instructions per sub-block and saves ten registers held across the loop.
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;                 // 1 KB aligned
+    const uint32_t k_base = smem_addr + (uint32_t)(c16 * ROWB + ((g4 ^ swizzle16(c16)) << 4));
+    // V (A operand of O^T += V^T P^T, 16 channels x 32 keys) through the transposing read: within each block of 16
+    // lanes, lane 4*j4 + s4 supplies 4 channels (4*s4..4*s4+3 of the block's 16) of key row 4*g4 + j4; lane i then
+    // receives channel i of those four rows.  The second read of a pair takes the rows 16 further down.
+    const int j4 = (lane & 15) >> 2, s4 = lane & 3;
+    const uint32_t v_base = smem_addr + (uint32_t)((4 * g4 + j4) * ROWB + (((s4 >> 1) ^ swizzle16(4 * g4 + j4)) << 4) + 8 * (s4 & 1));
+
+    // ---- Q fragments (B operand of S^T: query 16*qb + c16, channels 32*ks + 8*g4 ..), resident in registers.
+    // With PRESCALE they are multiplied by scale * log2(e) here, once, and rounded to bf16 again, so that the matrix
+    // product delivers base-2 exponents and the 16 multiplications per lane and sub-block disappear.  Measured
+    // 4.5 % faster (11.43 against 11.95 ms at 115,200 tokens, window 3x3x3), but the second rounding of Q puts a
+    // relative error of up to 2^-9 on every term of a score: with scores of a few tens the probabilities are off by
+    // a percent and the output error leaves the 2e-2 bound (0.07 on the growing-maximum test).  The entry points
+    // therefore use the exact form; the flag is kept for measurements.
+    bf16x8 Qr[2][KS];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 raw = *reinterpret_cast<const bf16x8 *>(qh + (size_t)(16 * qb + c16) * D + ks * 32 + g4 * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                Qr[qb][ks][e] = PRESCALE ? static_cast<__bf16>(static_cast<float>(raw[e]) * p.scale_log2e) : raw[e];
+        }
+
+    // O^T accumulators: Oacc[cb][qb][i] = channel 16*cb + 4*g4 + i of query 16*qb + c16
+    floatx4 Oacc[CB][2];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) Oacc[cb][qb] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // Offset m per query, in the units of the scores (raw dot products; base-2 exponents with PRESCALE).  The score
+    // accumulators START at -m (Sinit, the value replicated over the four registers of an accumulator), so what the
+    // matrix instructions deliver is s - m and the exponential needs one multiplication by scale * log2(e) per
+    // element instead of a fused multiply-add plus bookkeeping.  m is 0 for the first sub-block, which then always
+    // takes the re-basing path below, and never decreases afterwards.
+    float m_run[2] = {0.f, 0.f};
+    floatx4 Sinit[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
+    float l_run[2] = {0.f, 0.f};                  // this lane's share of the two row sums
+
+    const int sub_per_tile = p.P / KB;
+    const int n_all = box.count() * sub_per_tile;           // sub-blocks of the whole item
+    // (the 64-bit divisions are done in vector registers; the results are wave-uniform and go back to scalar ones)
+    const int iter_lo = is_part ? __builtin_amdgcn_readfirstlane((int)((long long)n_all * part / p.split_parts)) : 0;
+    const int n_iter = (is_part ? __builtin_amdgcn_readfirstlane((int)((long long)n_all * (part + 1) / p.split_parts)) : n_all) - iter_lo;
+    // Order in which the key tiles of the box are visited.  Along each axis the box [lo, hi] holds e = hi-lo+1
+    // consecutive tiles, hence exactly one tile of every residue class mod e; the walk takes them in the order
+    // of that residue (k mod e = 0, 1, ..), i.e. it starts inside the box and wraps from hi to lo.  Query tiles
+    // that are neighbours along an axis have boxes shifted by one tile: with this order they reach each key
+    // tile they share at the SAME step of their walks, so workgroups resident on an XCD at one time read the
+    // same K/V tiles at about the same time and find them in that XCD's L2.  (Walking every box from its own lo
+    // makes neighbours read a shared tile at different steps; the L2 is far too small to keep it that long.)
+    const int e_t = box.t.hi - box.t.lo + 1, e_h = box.h.hi - box.h.lo + 1, e_w = box.w.hi - box.w.lo + 1;
+    const int start_t = box.t.lo + (e_t - box.t.lo % e_t) % e_t;
+    const int start_h = box.h.lo + (e_h - box.h.lo % e_h) % e_h;
+    const int start_w = box.w.lo + (e_w - box.w.lo % e_w) % e_w;
+    int it_t = start_t, it_h = start_h, it_w = start_w, it_s = 0;
+    int left_h = e_h, left_w = e_w;         // tiles still to visit in the current h-cycle / w-cycle
+    auto row_start = [&]() -> size_t {      // byte offset of key tile (it_t, it_h, it_w) inside the head
+        const size_t kt = ((size_t)it_t * p.n_h + it_h) * p.n_w + it_w;
+        return kt * p.P * ROWB;
+    };
+    // a part starts iter_lo sub-blocks into the walk: whole tiles first, then sub-blocks inside the tile
+    for (int skip = iter_lo / sub_per_tile; skip > 0; --skip) {
+        if (++it_w > box.w.hi) it_w = box.w.lo;
+        if (--left_w == 0) {
+            left_w = e_w;
+            it_w = start_w;
+            if (++it_h > box.h.hi) it_h = box.h.lo;
+            if (--left_h == 0) {
+                left_h = e_h;
+                it_h = start_h;
+                if (++it_t > box.t.hi) it_t = box.t.lo;
+            }
+        }
+    }
+    it_s = iter_lo % sub_per_tile;
+    size_t next_base = row_start() + (size_t)it_s * KB * ROWB;
+    auto advance = [&]() {
+        next_base += (size_t)KB * ROWB;
+        if (++it_s == sub_per_tile) {
+            it_s = 0;
+            if (++it_w > box.w.hi) it_w = box.w.lo;
+            if (--left_w == 0) {
+                left_w = e_w;
+                it_w = start_w;
+                if (++it_h > box.h.hi) it_h = box.h.lo;
+                if (--left_h == 0) {
+                    left_h = e_h;
+                    it_h = start_h;
+                    if (++it_t > box.t.hi) it_t = box.t.lo;
+                }
+            }
+            next_base = row_start();
+        }
+    };
+
+    // The SIMD's arbiter prefers its oldest wave, and a wave whose next instruction is an MFMA waiting for the
+    // matrix pipe holds the vector issue port meanwhile: the softmax arithmetic of the younger waves of a SIMD
+    // then waits behind the older waves' matrix phases.  Static priorities against the age order (waves w, w+4,
+    // w+8 share a SIMD) even this out.  Measured in one call: 12.41 -> 12.22 ms, and 9.50 -> 9.24 ms on constant
+    // inputs, where the clock does not move.
+    if constexpr (NW == 12) {
+        if (wave >= 8) __builtin_amdgcn_s_setprio(2);
+        else if (wave >= 4) __builtin_amdgcn_s_setprio(1);
+    }
+
+    // ---- pipeline: up to STAGES-1 sub-blocks are in flight.  (it_t, it_h, it_w, it_s) always names the next
+    // sub-block to request; `issued` counts the requests made so far.
+    int issued = 0;
+    auto issue_next = [&]() {
+        if (issued < n_iter) {
+            if (wave < LOADERS) issue_loads(issued % STAGES, next_base);
+            advance();
+            ++issued;
+        }
+    };
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue_next();
+
+    // One sub-block.  The loop is not unrolled over the two stages (unrolled, the register allocator gives the
+    // accumulators different registers in the two copies and copies all 64 once per pair of sub-blocks); the stage
+    // enters the two operand base addresses with one addition each.
+    constexpr int KOFF = 0, VOFF = TILE_BYTES;
+    // units of the accumulated scores: base-2 exponents if Q was scaled, raw dot products otherwise
+    const float c = PRESCALE ? 1.f : p.scale_log2e;
+    auto sub_block = [&](int stage, float grow_above) {
+        // this wave's DMA for this sub-block must have landed (the only requests outstanding)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();   // ... and everyone's; the stage read in the previous iteration is free again
+        issue_next();      // refills stage (iter - 1) % STAGES
+
+        // ---- S^T = K Q^T: four 16x16 blocks (two key blocks x two query blocks), four k-steps of 32 channels each.
+        // K-operand reads are issued by hand, one key block ahead of the MFMAs.
+        floatx4 S[2][2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) S[kb][qb] = Sinit[qb];
+        const uint32_t kb_ = k_base + (uint32_t)(stage * STAGE_BYTES), vb_ = v_base + (uint32_t)(stage * STAGE_BYTES);
+        auto k_read = [&](auto kbc, auto ksc) {
+            return ds_read_b128_at<KOFF + decltype(kbc)::value * 16 * ROWB>(kb_ ^ (uint32_t)(decltype(ksc)::value << 6));
+        };
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using I2 = std::integral_constant<int, 2>;
+        using I3 = std::integral_constant<int, 3>;
+        // six reads in flight at most; the second key block's last two fragments reuse the registers of the first's
+        bf16x8 a0 = k_read(I0{}, I0{}), a1 = k_read(I0{}, I1{}), a2 = k_read(I0{}, I2{}), a3 = k_read(I0{}, I3{});
+        bf16x8 b0 = k_read(I1{}, I0{}), b1 = k_read(I1{}, I1{});
+        lds_wait2<4>(a0, a1);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) S[0][qb] = mfma_16x16x32(a0, Qr[qb][0], S[0][qb]);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) S[0][qb] = mfma_16x16x32(a1, Qr[qb][1], S[0][qb]);
+        __builtin_amdgcn_sched_barrier(0);   // keep each MFMA group ahead of the next group's reads and wait
+        bf16x8 b2 = k_read(I1{}, I2{}), b3 = k_read(I1{}, I3{});
+        lds_wait2<4>(a2, a3);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) S[0][qb] = mfma_16x16x32(a2, Qr[qb][2], S[0][qb]);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) S[0][qb] = mfma_16x16x32(a3, Qr[qb][3], S[0][qb]);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_wait2<2>(b0, b1);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) S[1][qb] = mfma_16x16x32(b0, Qr[qb][0], S[1][qb]);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) S[1][qb] = mfma_16x16x32(b1, Qr[qb][1], S[1][qb]);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_wait2<0>(b2, b3);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) S[1][qb] = mfma_16x16x32(b2, Qr[qb][2], S[1][qb]);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) S[1][qb] = mfma_16x16x32(b3, Qr[qb][3], S[1][qb]);
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- online softmax.  A lane holds, for each of its two queries, 8 of the 32 scores (keys 4*g4 + i of both
+        // key blocks); the other 24 sit in the lanes 16, 32 and 48 further on.  The offset only moves when a score
+        // exceeds it by more than 2^8 in the exponent (lazy re-basing), which after the first sub-blocks is rare: the
+        // common path takes one maximum over the lane's 16 values and one comparison, with no exchange between
+        // lanes; only when some lane reports growth is the row maximum formed over the four lanes of a query, so
+        // that all of them move to the same offset.  grow_above is that bound in the units of the scores, or -infinity
+        // in an item's first sub-block.
+        float mq[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            mq[qb] = max3(S[0][qb][0], S[0][qb][1], S[0][qb][2]);
+            mq[qb] = max3(mq[qb], S[0][qb][3], S[1][qb][0]);
+            mq[qb] = max3(mq[qb], S[1][qb][1], S[1][qb][2]);
+        }
+        const float mx = max3(max3(mq[0], S[1][0][3], mq[1]), S[1][1][3], S[1][1][3]);
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > grow_above) != 0, 0)) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                const float row_max = quad_lane_max(fmaxf(mq[qb], S[1][qb][3]));
+                const float shift = row_max > grow_above ? row_max : 0.f;     // the same in the four lanes of a query
+                // shift is negative only in a first sub-block, where the accumulators are still zero
+                const float alpha = __builtin_amdgcn_exp2f(fminf(-shift, 0.f) * c);
+                m_run[qb] += shift;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) Sinit[qb][r] = -m_run[qb];
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) S[kb][qb][r] -= shift;
+                l_run[qb] *= alpha;
+                // in place: written as plain multiplications the register allocator gives the scaled accumulators
+                // new registers and then copies all 64 on the path that does NOT rescale
+                // (the compiler does not see into the assembly: the wait state that a vector instruction needs before
+                // it reads the result of a transcendental one is given by hand)
+                float alpha_settled = alpha;
+                asm volatile("s_nop 1" : "+v"(alpha_settled));
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) scale_in_place(Oacc[cb][qb], alpha_settled);
+            }
+        }
+        // first group of V-operand reads (channel blocks 0..3) goes out once the offsets are settled (no
+        // earlier: their sixteen registers would be live across the rescaling branch); the exponentials hide its latency
+        shortx4 va[2][4][2];
+        static_for<0, 4>([&](auto i) {
+            constexpr int cb = decltype(i)::value;
+            va[0][cb][0] = ds_read_tr16<VOFF>(vb_ ^ (uint32_t)(cb << 5));
+            va[0][cb][1] = ds_read_tr16<VOFF + 16 * ROWB>(vb_ ^ (uint32_t)(cb << 5));
+        });
+        __builtin_amdgcn_sched_barrier(0);       // the exponentials stay behind these reads
+        // probabilities, rounded to bf16, packed as the B operand of the PV product of their query block: k index
+        // 8*g4 + i of that product is key 4*g4 + i of the first key block (i < 4) or of the second (i >= 4)
+        bf16x8 Pb[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int e = 0; e < 4; e += 2) {
+                    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                    const float p0 = __builtin_amdgcn_exp2f(PRESCALE ? S[kb][qb][e] : S[kb][qb][e] * c);
+                    const float p1 = __builtin_amdgcn_exp2f(PRESCALE ? S[kb][qb][e + 1] : S[kb][qb][e + 1] * c);
+                    bf16x2 pp;
+                    pp[0] = static_cast<__bf16>(p0);
+                    pp[1] = static_cast<__bf16>(p1);
+                    Pb[qb][4 * kb + e] = pp[0];
+                    Pb[qb][4 * kb + e + 1] = pp[1];
+                    bf16x2 ones;
+                    ones[0] = static_cast<__bf16>(1.0f);
+                    ones[1] = static_cast<__bf16>(1.0f);
+                    l_run[qb] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run[qb], false);   // sums the rounded values
+                }
+        }
+
+        // ---- O^T += V^T P^T: one k-step covers the 32 keys; eight channel blocks x two query blocks.  The transposing
+        // reads are issued by hand, four channel blocks ahead of the MFMAs that consume them.
+        static_for<0, 2>([&](auto gi) {
+            constexpr int g = decltype(gi)::value;
+            if constexpr (g == 0) {
+                static_for<0, 4>([&](auto i) {
+                    constexpr int cb = 4 + decltype(i)::value;
+                    va[1][cb - 4][0] = ds_read_tr16<VOFF>(vb_ ^ (uint32_t)(cb << 5));
+                    va[1][cb - 4][1] = ds_read_tr16<VOFF + 16 * ROWB>(vb_ ^ (uint32_t)(cb << 5));
+                });
+                pv_wait<8>(va[0]);
+            } else {
+                pv_wait<0>(va[1]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                typedef short shortx8 __attribute__((ext_vector_type(8)));
+                const shortx8 v01 = __builtin_shufflevector(va[g][i][0], va[g][i][1], 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+                    Oacc[4 * g + i][qb] = mfma_16x16x32(__builtin_bit_cast(bf16x8, v01), Pb[qb], Oacc[4 * g + i][qb]);
+            }
+            if constexpr (g == 0) __builtin_amdgcn_sched_barrier(0);   // the second group's wait stays behind these MFMAs
+        });
+    };
+
+#pragma unroll 1
+    for (int iter = 0; iter < n_iter; ++iter) {
+        // growth threshold: 2^8 in the units of the scores, -infinity in the first sub-block
+        const uint32_t thr = __builtin_amdgcn_readfirstlane(iter == 0 ? 0xff800000u : __float_as_uint(8.0f / c));
+        sub_block(iter & 1, __uint_as_float(thr));
+    }
+
+    // ---- finalize -------------------------------------------------------------------
+    float l_tot[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) l_tot[qb] = quad_lane_sum(l_run[qb]);
+    if (is_part) {
+        // unnormalised accumulator, offset and row sum of this part; the combine kernel does the rest
+        float *ws = p.split_ws + (size_t)(blockIdx.x - p.split_first) * split_part_floats<D>(QB);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            float *wo = ws + (size_t)(wave * 32 + 16 * qb + c16) * D;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) *reinterpret_cast<floatx4 *>(wo + 16 * cb + 4 * g4) = Oacc[cb][qb];
+            if (g4 == 0) {
+                ws[(size_t)QB * D + wave * 32 + 16 * qb + c16] = m_run[qb] * c;      // the merge takes base-2 units
+                ws[(size_t)QB * D + QB + wave * 32 + 16 * qb + c16] = l_tot[qb];
+            }
+        }
+        return;
+    }
+    bf16_raw *oh = o + (bh * p.N + (size_t)qblock * QB + (size_t)wave * 32) * D;
+    // sum_j exp(s_j * scale) = 2^m * l  =>  ln = m * ln 2 + ln l
+    if (p.lse != nullptr && g4 == 0) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+            p.lse[bh * p.N + (size_t)qblock * QB + (size_t)wave * 32 + 16 * qb + c16] =
+                m_run[qb] * c * 0.6931471805599453f + __logf(l_tot[qb]);
+    }
+    // The rows go through LDS (each wave its own 32 rows; 16-byte chunk c of row r at position c ^ (r & 15)) and leave
+    // as whole rows, 1 KB contiguous per store instruction, with streaming stores.
+    __syncthreads();                                   // every wave has finished reading the K/V stages
+    char *rows = smem + wave * (32 * ROWB);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const float inv = 1.f / l_tot[qb];
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            bf16x4 ov;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ov[t] = static_cast<__bf16>(Oacc[cb][qb][t] * inv);
+            const int chunk = 2 * cb + (g4 >> 1);
+            *reinterpret_cast<bf16x4 *>(rows + (16 * qb + c16) * ROWB + ((chunk ^ c16) << 4) + 8 * (g4 & 1)) = ov;
+        }
+    }
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int i = 0; i < 32 / RPI; ++i) {
+        const int r = RPI * i + lane / LPR, cpos = lane % LPR;
+        const u32x4 x = *reinterpret_cast<const u32x4 *>(rows + r * ROWB + ((cpos ^ (r & (LPR - 1))) << 4));
+        __builtin_nontemporal_store(x, reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(oh) + (size_t)r * ROWB + (cpos << 4)));
+    }
+}
+
 // Merges the parts of every split item: one wave per query row, two channels per lane.  With m the largest of
-// the parts' offsets:  O = sum_j 2^((m_j - m) c) O_j / sum_j 2^((m_j - m) c) l_j, parts taken in ascending order.
+// the parts' offsets (base-2 units):  O = sum_j 2^(m_j - m) O_j / sum_j 2^(m_j - m) l_j, parts in ascending order.
 template <int D, int QB>
 __global__ __launch_bounds__(256) void sta_fwd_combine_kernel(bf16_raw *__restrict__ o, sta::FwdParams p,
                                                               sta::HeadOrder order, uint32_t n_bh)
@@ -789,13 +1233,12 @@ __global__ __launch_bounds__(256) void sta_fwd_combine_kernel(bf16_raw *__restri
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);       // query inside the block
     const int lane = threadIdx.x & 63;
     const float *ws = p.split_ws + (size_t)blockIdx.y * p.split_parts * split_part_floats<D>(QB);
-    const float c = p.scale_log2e;
     float m = -INFINITY;
     for (uint32_t j = 0; j < p.split_parts; ++j) m = fmaxf(m, ws[j * split_part_floats<D>(QB) + (size_t)QB * D + row]);
     float l = 0.f, a0 = 0.f, a1 = 0.f;
     for (uint32_t j = 0; j < p.split_parts; ++j) {
         const float *part = ws + j * split_part_floats<D>(QB);
-        const float w = exp2f((part[(size_t)QB * D + row] - m) * c);
+        const float w = exp2f(part[(size_t)QB * D + row] - m);
         l += w * part[(size_t)QB * D + QB + row];
         const float2 x = *reinterpret_cast<const float2 *>(part + (size_t)row * D + 2 * lane);
         a0 += w * x.x;
@@ -808,7 +1251,7 @@ __global__ __launch_bounds__(256) void sta_fwd_combine_kernel(bf16_raw *__restri
     ov[0] = static_cast<__bf16>(a0 * inv);
     ov[1] = static_cast<__bf16>(a1 * inv);
     *reinterpret_cast<bf16x2 *>(o + out_row * D + 2 * lane) = ov;
-    if (p.lse != nullptr && lane == 0) p.lse[out_row] = m * c * 0.6931471805599453f + __logf(l);
+    if (p.lse != nullptr && lane == 0) p.lse[out_row] = m * 0.6931471805599453f + __logf(l);
 }
 
 // Host side of the work splitting: how many workgroups the chip holds at once.
@@ -825,7 +1268,7 @@ inline uint32_t resident_workgroups(int minb)
     return (uint32_t)cus * (uint32_t)minb;
 }
 
-template <int D, int NW, int KB, int STAGES, int MINB>
+template <int D, int NW, int KB, int STAGES, int MINB, bool X32 = false, bool PRESCALE = false>
 hipError_t launch_fast(const void *q, const void *k, const void *v, void *o, int B, const sta::FwdParams &p_in,
                             const sta::WindowTable &win, const sta::HeadOrder &order, float *split_ws,
                             size_t split_ws_floats, hipStream_t stream)
@@ -881,9 +1324,16 @@ hipError_t launch_fast(const void *q, const void *k, const void *v, void *o, int
         }
     }
     dim3 grid(p.split_first + split_items * p.split_parts), block(NW * 64);
-    sta_fwd_fast_kernel<D, NW, KB, STAGES, MINB><<<grid, block, 0, stream>>>(
-        static_cast<const bf16_raw *>(q), static_cast<const bf16_raw *>(k), static_cast<const bf16_raw *>(v),
-        static_cast<bf16_raw *>(o), p, win, order, n_bh);
+    if constexpr (X32) {
+        static_assert(D == 128 && KB == 32, "the 16x16x32 kernel exists for head dimension 128 only");
+        sta_fwd_x32_kernel<NW, STAGES, MINB, PRESCALE><<<grid, block, 0, stream>>>(
+            static_cast<const bf16_raw *>(q), static_cast<const bf16_raw *>(k), static_cast<const bf16_raw *>(v),
+            static_cast<bf16_raw *>(o), p, win, order, n_bh);
+    } else {
+        sta_fwd_fast_kernel<D, NW, KB, STAGES, MINB><<<grid, block, 0, stream>>>(
+            static_cast<const bf16_raw *>(q), static_cast<const bf16_raw *>(k), static_cast<const bf16_raw *>(v),
+            static_cast<bf16_raw *>(o), p, win, order, n_bh);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split_items == 0) return e;
     if constexpr (D == 128) {
@@ -974,9 +1424,9 @@ hipError_t launch_forward(const void *q, const void *k, const void *v, void *o, 
     // 3x3x3: 12.8-13.1 ms against 13.6-13.7 ms for the 4-wave shape in the same session; 2 LDS stages were
     // faster than 3 (13.15 ms) or 4 (13.3 ms).
     if (p.P % 384 == 0)
-        return launch_fast<128, 12, 32, 2, 1>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
+        return launch_fast<128, 12, 32, 2, 1, true>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
     if (p.P % 128 == 0)
-        return launch_fast<128, 4, 32, 2, 3>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
+        return launch_fast<128, 4, 32, 2, 3, true>(q, k, v, o, B, p, win, order, split_ws, split_ws_floats, stream);
     return launch_d<128>(q, k, v, o, B, p, win, stream);
 }
 

@@ -19,6 +19,11 @@ __device__ __forceinline__ floatx16 mfma_32x32x16(bf16x8 a, bf16x8 b, floatx16 c
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+__device__ __forceinline__ floatx4 mfma_16x16x32(bf16x8 a, bf16x8 b, floatx4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 #define STA_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
@@ -41,6 +46,31 @@ __device__ __forceinline__ float half_swap_sum(float x)
 {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Maximum / sum over the four lanes l, l^16, l^32, l^48 (the lanes that hold one column of a 16x16 MFMA result):
+// v_permlane32_swap pairs lanes 32 apart, v_permlane16_swap lanes 16 apart; every lane ends with the same value.
+__device__ __forceinline__ float quad_lane_max(float x)
+{
+    const float a = half_swap_max(x);
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(a), false, false);
+    const float u = __uint_as_float(r[0]), w = __uint_as_float(r[1]);
+    return max3(u, w, w);
+}
+
+__device__ __forceinline__ float quad_lane_sum(float x)
+{
+    const float a = half_swap_sum(x);
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(a), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// x *= a with the result forced into the registers of x.
+__device__ __forceinline__ void scale_in_place(floatx4 &x, float a)
+{
+    asm volatile("v_mul_f32_e32 %0, %4, %0\n\tv_mul_f32_e32 %1, %4, %1\n\tv_mul_f32_e32 %2, %4, %2\n\tv_mul_f32_e32 %3, %4, %3"
+                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3])
+                 : "v"(a));
 }
 
 template <int I, int N, typename F>
@@ -99,6 +129,12 @@ template <int PENDING>
 __device__ __forceinline__ void k_wait(bf16x8 (&ka)[4])
 {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(ka[0]), "+v"(ka[1]), "+v"(ka[2]), "+v"(ka[3]) : "n"(PENDING));
+}
+
+template <int PENDING>
+__device__ __forceinline__ void lds_wait2(bf16x8 &a, bf16x8 &b)
+{
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(PENDING));
 }
 
 // Wait until at most PENDING LDS reads are outstanding; the operands are tied to the wait so that
