@@ -783,19 +783,25 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_
 // two waves per SIMD: 2019 TFLOP/s against 1784 (equal, 2440, on constant operands).
 // Layout: a lane holds column c16 = lane & 15 of a 16x16 result (a query) and rows 4*g4 .. 4*g4+3 (g4 = lane >> 4);
 // of an operand it holds row/column c16 and the k-chunk 8*g4 .. 8*g4+7.  A wave's 32 queries are two query blocks;
-// every K and V fragment read from LDS feeds both.  One swizzle serves the row reads of K and the transposing reads
-// of V: 16-byte chunk c of row r sits at position c ^ swizzle16(r), swizzle16(r) = 2 * (r & 7).  Why this one (all
-// rows start at bank 0, a row being 256 bytes = the 64 banks):
-//  - a transposing 8-byte read is served 32 lanes at a time; those lanes read 8 consecutive rows, two neighbouring
-//    chunks (2*cb, 2*cb + 1) of each: the rows' swizzles must differ above bit 0;
-//  - a 16-byte read is served 16 lanes at a time, and measured with the bank-conflict counter those 16 are not
-//    consecutive lanes but lanes 0-7 together with lanes 24-31 (then 8-15 with 16-23, and the same in the upper
-//    half): rows 0..7 at chunk x and rows 8..15 at chunk x ^ 1.  The two sets of positions x ^ swizzle16(0..7) and
-//    x ^ 1 ^ swizzle16(8..15) are the even and the odd ones: disjoint.
-// (The bijective 4-bit swizzles that look right for 16 consecutive lanes cost a 2-way conflict on every K read.)
-__device__ __forceinline__ constexpr int swizzle16(int r) { return (r & 7) << 1; }
+// every K and V fragment read from LDS feeds both.
+// LDS layout of a staged sub-block: groups of 4 rows (1 KB, what one DMA instruction fills), the groups
+// kKGroup = 1024 + 64 bytes apart for K and kVGroup = 1024 + 32 bytes apart for V; inside a group the 16-byte chunk c
+// of row j (0..3) sits at position c ^ j for K and c ^ (j << 2) for V.  A row is 256 bytes = all 64 banks, so the
+// rows of a group start at the same bank and it is the XOR that keeps them apart, while the padding turns
+// consecutive groups by 16 (K) or 8 (V) banks.  Measured with the bank-conflict counter, both reads are free of
+// conflicts:
+//  - a 16-byte read is served 16 lanes at a time, and those are not 16 consecutive lanes but lanes 0-7 together
+//    with lanes 24-31 (then 8-15 with 16-23, and the same in the upper half): rows 0..7 at chunk x, rows 8..15 at
+//    chunk x ^ 1.  Four groups of four rows, each group in its own 64 bytes of the 256;
+//  - a transposing 8-byte read is served 32 lanes at a time: 8 consecutive rows, two neighbouring chunks of each.
+//    The rows of a group take different quarters of the 256 bytes, the second group the other 32 bytes of each.
+// The point of this layout over a plain XOR swizzle of whole rows: the k-step of a K read (64 bytes) and the odd
+// channel blocks of a V read (32 bytes) are offsets that go into the instruction, and the XOR touches only two
+// address bits of V.  Per sub-block that leaves five address computations where a whole-row swizzle needs
+// thirteen, and on this chip every vector instruction saved is energy, hence time.
+constexpr int kKGroup = 1024 + 64, kVGroup = 1024 + 32;
 
-template <int NW, int STAGES, int MINB, bool PRESCALE>
+template <int NW, int KB, int STAGES, int MINB, bool PRESCALE>
 __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_raw *__restrict__ q,
                                                                  const bf16_raw *__restrict__ k,
                                                                  const bf16_raw *__restrict__ v,
@@ -803,14 +809,16 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
                                                                  sta::WindowTable win, sta::HeadOrder order,
                                                                  uint32_t n_bh)
 {
-    constexpr int D = 128, KB = 32;
+    constexpr int D = 128;
+    static_assert(KB == 32, "keys per sub-block");
     constexpr int QB = NW * 32;                    // queries per workgroup: one 32-query block per wave
     constexpr int KS = D / 32;                     // k-steps of 32 channels in S^T = K Q^T
     constexpr int CB = D / 16;                     // 16-channel blocks of O^T
     constexpr int ROWB = D * 2;                    // bytes per key row in LDS
-    constexpr int TILE_BYTES = KB * ROWB;          // one K (or V) sub-block
-    constexpr int STAGE_BYTES = 2 * TILE_BYTES;    // K then V
-    constexpr int INSTR = TILE_BYTES / 1024;       // 1 KB DMA instructions per operand per sub-block
+    constexpr int GROUPS = KB / 4;                 // 4-row groups of a sub-block = DMA instructions per operand
+    constexpr int K_BYTES = GROUPS * kKGroup, V_BYTES = GROUPS * kVGroup;
+    constexpr int STAGE_BYTES = K_BYTES + V_BYTES; // K then V
+    constexpr int INSTR = GROUPS;
     constexpr int WANT_LOADERS = NW < 4 ? NW : (NW < 8 ? 4 : 8);
     constexpr int LOADERS = WANT_LOADERS < INSTR ? WANT_LOADERS : INSTR;     // waves 0 .. LOADERS-1 issue the DMA
     constexpr int LOADS = INSTR / LOADERS;         // ... this many instructions per operand each
@@ -851,48 +859,44 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
     const char *kh = reinterpret_cast<const char *>(k + bh * p.N * D);
     const char *vh = reinterpret_cast<const char *>(v + bh * p.N * D);
 
-    // ---- DMA loads.  Each wave-wide 16 B/lane instruction fills 1 KB of LDS = RPI consecutive key rows (a
-    // lane's LDS slot is fixed by the hardware: base + 16*lane), so the swizzle is applied on the global side: the
-    // lane fetches the logical chunk that belongs at its slot.  The KB keys of a sub-block are taken as blocks of
-    // 16 rows; loading wave w fetches rows RPI*(w%IPB) .. +RPI-1 of the blocks LOADS*(w/IPB) .. +LOADS-1, one
-    // instruction per block.  Both swizzles depend on the row only through row & 15, so a lane's offset inside
-    // its block is the same for all its instructions and the rest of the address is wave-uniform: one 32-bit
-    // lane offset per operand on top of a scalar base, and no vector arithmetic per load.
-    uint32_t kv_lane_off;                           // K and V share one swizzle here
-    {
-        const int lrow = RPI * (wave % IPB) + lane / LPR;   // row & 15 of every row this lane fetches
-        const int slot = lane % LPR;
-        kv_lane_off = (uint32_t)(lrow * ROWB + ((slot ^ swizzle16(lrow)) << 4));
-    }
+    // ---- DMA loads.  Each wave-wide 16 B/lane instruction fills 1 KB of LDS = one group of 4 key rows (a lane's
+    // LDS slot is fixed by the hardware: base + 16*lane), so the XOR is applied on the global side: the lane
+    // fetches the logical chunk that belongs at its slot.  Loading wave w takes the groups LOADS*w .. +LOADS-1.
+    // A lane's offset inside its group is the same for all its instructions and the rest of the address is
+    // wave-uniform: one 32-bit lane offset per operand on top of a scalar base, no vector arithmetic per load.
+    static_assert(RPI == 4 && LPR == 16, "a DMA instruction fills one group of four rows");
+    const uint32_t k_lane_off = (uint32_t)((lane >> 4) * ROWB + (((lane & 15) ^ (lane >> 4)) << 4));
+    const uint32_t v_lane_off = (uint32_t)((lane >> 4) * ROWB + (((lane & 15) ^ ((lane >> 4) << 2)) << 4));
     auto issue_loads = [&](int stage, size_t key_byte_base) {
         char *sdst = smem + stage * STAGE_BYTES;                           // only waves < LOADERS get here
-        uint32_t koff = kv_lane_off;
-        asm volatile("" : "+v"(koff));                  // keep the lane offset 32-bit next to a scalar base
-        const uint32_t voff = koff;
+        uint32_t koff = k_lane_off, voff = v_lane_off;
+        asm volatile("" : "+v"(koff), "+v"(voff));      // keep the lane offsets 32-bit next to a scalar base
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
-            const int block16 = LOADS * (wave / IPB) + i;
-            const size_t gbase = key_byte_base + (size_t)block16 * (16 * ROWB);
-            char *kdst = sdst + (16 * block16 + RPI * (wave % IPB)) * ROWB;
+            const int group = LOADS * wave + i;
+            const size_t gbase = key_byte_base + (size_t)group * (4 * ROWB);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + gbase + koff),
-                                             STA_LDS_PTR(kdst), 16, 0, 0);
+                                             STA_LDS_PTR(sdst + group * kKGroup), 16, 0, 0);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + gbase + voff),
-                                             STA_LDS_PTR(kdst + TILE_BYTES), 16, 0, 0);
+                                             STA_LDS_PTR(sdst + K_BYTES + group * kVGroup), 16, 0, 0);
         }
     };
 
-    // ---- per-lane constants of the operand reads
-    // K (A operand of S^T = K Q^T, 16 keys x 32 channels): key row 16*kb + c16, logical chunk 4*ks + g4
-    // The addresses of the other k-steps / channel blocks differ from the first one's only in bits that the
-    // swizzle XORs, so they are formed from one base per operand with one XOR each where they are used, which costs
-    // a few vector instructions per sub-block and saves ten registers held across the loop.
-    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;                 // 1 KB aligned
-    const uint32_t k_base = smem_addr + (uint32_t)(c16 * ROWB + ((g4 ^ swizzle16(c16)) << 4));
+    // ---- per-lane constants of the operand reads (stage 0; the stage is added where they are used)
+    // K (A operand of S^T = K Q^T, 16 keys x 32 channels): key row 16*kb + c16 = row c16 & 3 of group 4*kb + (c16 >> 2),
+    // logical chunk 4*ks + g4.  The XOR reaches only the two low bits of the chunk, so kb and ks are immediates.
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
+    const uint32_t k_base = smem_addr + (uint32_t)((c16 >> 2) * kKGroup + (c16 & 3) * ROWB + ((g4 ^ (c16 & 3)) << 4));
     // V (A operand of O^T += V^T P^T, 16 channels x 32 keys) through the transposing read: within each block of 16
-    // lanes, lane 4*j4 + s4 supplies 4 channels (4*s4..4*s4+3 of the block's 16) of key row 4*g4 + j4; lane i then
-    // receives channel i of those four rows.  The second read of a pair takes the rows 16 further down.
+    // lanes, lane 4*j4 + s4 supplies 4 channels (4*s4..4*s4+3 of the block's 16) of key row 4*g4 + j4 = row j4 of
+    // group g4; lane i then receives channel i of those four rows.  The second read of a pair takes the rows 16
+    // (four groups) further down.  Logical chunk 2*cb + (s4 >> 1): the XOR with j4 << 2 reaches the two high bits
+    // of the chunk = cb >> 1, one address per value of it; cb & 1 is 32 bytes in the instruction.
     const int j4 = (lane & 15) >> 2, s4 = lane & 3;
-    const uint32_t v_base = smem_addr + (uint32_t)((4 * g4 + j4) * ROWB + (((s4 >> 1) ^ swizzle16(4 * g4 + j4)) << 4) + 8 * (s4 & 1));
+    uint32_t v_addr[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+        v_addr[m] = smem_addr + (uint32_t)(K_BYTES + g4 * kVGroup + j4 * ROWB + ((((m ^ j4) << 2) | (s4 >> 1)) << 4) + 8 * (s4 & 1));
 
     // ---- Q fragments (B operand of S^T: query 16*qb + c16, channels 32*ks + 8*g4 ..), resident in registers.
     // With PRESCALE they are multiplied by scale * log2(e) here, once, and rounded to bf16 again, so that the matrix
@@ -1009,16 +1013,15 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
 
     // One sub-block.  The loop is not unrolled over the two stages (unrolled, the register allocator gives the
     // accumulators different registers in the two copies and copies all 64 once per pair of sub-blocks); the stage
-    // enters the two operand base addresses with one addition each.
-    constexpr int KOFF = 0, VOFF = TILE_BYTES;
+    // enters the five operand base addresses with one addition each.
+    // (lds_off: where the stage begins; it enters the operand base addresses at run time)
     // units of the accumulated scores: base-2 exponents if Q was scaled, raw dot products otherwise
     const float c = PRESCALE ? 1.f : p.scale_log2e;
-    auto sub_block = [&](int stage, float grow_above) {
-        // this wave's DMA for this sub-block must have landed (the only requests outstanding)
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();   // ... and everyone's; the stage read in the previous iteration is free again
-        issue_next();      // refills stage (iter - 1) % STAGES
-
+    auto half_block = [&](uint32_t lds_off, float grow_above) {
+        const uint32_t kb_ = k_base + lds_off;
+        uint32_t vb_[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) vb_[m] = v_addr[m] + lds_off;
         // ---- S^T = K Q^T: four 16x16 blocks (two key blocks x two query blocks), four k-steps of 32 channels each.
         // K-operand reads are issued by hand, one key block ahead of the MFMAs.
         floatx4 S[2][2];
@@ -1026,9 +1029,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) S[kb][qb] = Sinit[qb];
-        const uint32_t kb_ = k_base + (uint32_t)(stage * STAGE_BYTES), vb_ = v_base + (uint32_t)(stage * STAGE_BYTES);
         auto k_read = [&](auto kbc, auto ksc) {
-            return ds_read_b128_at<KOFF + decltype(kbc)::value * 16 * ROWB>(kb_ ^ (uint32_t)(decltype(ksc)::value << 6));
+            return ds_read_b128_at<decltype(kbc)::value * 4 * kKGroup + decltype(ksc)::value * 64>(kb_);
         };
         using I0 = std::integral_constant<int, 0>;
         using I1 = std::integral_constant<int, 1>;
@@ -1096,8 +1098,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
                 // new registers and then copies all 64 on the path that does NOT rescale
                 // (the compiler does not see into the assembly: the wait state that a vector instruction needs before
                 // it reads the result of a transcendental one is given by hand)
-                float alpha_settled = alpha;
-                asm volatile("s_nop 1" : "+v"(alpha_settled));
+                const float alpha_settled = settled_after_transcendental(alpha);
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) scale_in_place(Oacc[cb][qb], alpha_settled);
             }
@@ -1107,8 +1108,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
         shortx4 va[2][4][2];
         static_for<0, 4>([&](auto i) {
             constexpr int cb = decltype(i)::value;
-            va[0][cb][0] = ds_read_tr16<VOFF>(vb_ ^ (uint32_t)(cb << 5));
-            va[0][cb][1] = ds_read_tr16<VOFF + 16 * ROWB>(vb_ ^ (uint32_t)(cb << 5));
+            va[0][cb][0] = ds_read_tr16<(cb & 1) * 32>(vb_[cb >> 1]);
+            va[0][cb][1] = ds_read_tr16<(cb & 1) * 32 + 4 * kVGroup>(vb_[cb >> 1]);
         });
         __builtin_amdgcn_sched_barrier(0);       // the exponentials stay behind these reads
         // probabilities, rounded to bf16, packed as the B operand of the PV product of their query block: k index
@@ -1142,8 +1143,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
             if constexpr (g == 0) {
                 static_for<0, 4>([&](auto i) {
                     constexpr int cb = 4 + decltype(i)::value;
-                    va[1][cb - 4][0] = ds_read_tr16<VOFF>(vb_ ^ (uint32_t)(cb << 5));
-                    va[1][cb - 4][1] = ds_read_tr16<VOFF + 16 * ROWB>(vb_ ^ (uint32_t)(cb << 5));
+                    va[1][cb - 4][0] = ds_read_tr16<(cb & 1) * 32>(vb_[cb >> 1]);
+                    va[1][cb - 4][1] = ds_read_tr16<(cb & 1) * 32 + 4 * kVGroup>(vb_[cb >> 1]);
                 });
                 pv_wait<8>(va[0]);
             } else {
@@ -1161,11 +1162,15 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
         });
     };
 
+    const uint32_t bound_bits = __builtin_amdgcn_readfirstlane(__float_as_uint(8.0f / c));
 #pragma unroll 1
     for (int iter = 0; iter < n_iter; ++iter) {
-        // growth threshold: 2^8 in the units of the scores, -infinity in the first sub-block
-        const uint32_t thr = __builtin_amdgcn_readfirstlane(iter == 0 ? 0xff800000u : __float_as_uint(8.0f / c));
-        sub_block(iter & 1, __uint_as_float(thr));
+        // this wave's DMA for this sub-block must have landed (the only requests outstanding)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();   // ... and everyone's; the stage read in the previous iteration is free again
+        issue_next();      // refills stage (iter - 1) % STAGES
+        // growth threshold: 2^8 in the units of the scores, -infinity for the first keys of an item
+        half_block((uint32_t)((iter & 1) * STAGE_BYTES), __uint_as_float(iter == 0 ? 0xff800000u : bound_bits));
     }
 
     // ---- finalize -------------------------------------------------------------------
@@ -1325,8 +1330,8 @@ hipError_t launch_fast(const void *q, const void *k, const void *v, void *o, int
     }
     dim3 grid(p.split_first + split_items * p.split_parts), block(NW * 64);
     if constexpr (X32) {
-        static_assert(D == 128 && KB == 32, "the 16x16x32 kernel exists for head dimension 128 only");
-        sta_fwd_x32_kernel<NW, STAGES, MINB, PRESCALE><<<grid, block, 0, stream>>>(
+        static_assert(D == 128, "the 16x16x32 kernel exists for head dimension 128 only");
+        sta_fwd_x32_kernel<NW, KB, STAGES, MINB, PRESCALE><<<grid, block, 0, stream>>>(
             static_cast<const bf16_raw *>(q), static_cast<const bf16_raw *>(k), static_cast<const bf16_raw *>(v),
             static_cast<bf16_raw *>(o), p, win, order, n_bh);
     } else {

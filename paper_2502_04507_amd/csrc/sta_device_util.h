@@ -65,6 +65,14 @@ __device__ __forceinline__ float quad_lane_sum(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// The value, usable by hand-written vector instructions: the compiler does not see into inline assembly and so
+// cannot give such an instruction the wait state the hardware needs behind a transcendental one that produced x.
+__device__ __forceinline__ float settled_after_transcendental(float x)
+{
+    asm volatile("s_nop 1" : "+v"(x));
+    return x;
+}
+
 // x *= a with the result forced into the registers of x.
 __device__ __forceinline__ void scale_in_place(floatx4 &x, float a)
 {
