@@ -203,6 +203,21 @@ def test_attention_large_scores_stay_finite():
     gu.assert_parity(out[0, 0], ref, "bigscores")
 
 
+@pytest.mark.parametrize("tile,grid,D", [((6, 8, 8), (6, 16, 16), 128), ((2, 8, 8), (4, 16, 16), 128), ((6, 8, 8), (6, 8, 16), 64)])
+def test_attention_all_scores_far_below_zero(tile, grid, D):
+    """Every score of a row is a large negative number (positive queries, negative keys, a few hundred before
+    scaling): an exponent offset that starts at zero and is not moved DOWN by the first keys makes every
+    probability underflow and the row sum zero.  All three kernel shapes."""
+    w = syn.custom("negscores", 1, 2, D, grid, tile, [(1, 1, 2), (1, 2, 2)], "bf16", seed=83)
+    q, k, v = syn.make_qkv(w)
+    q = (q.float().abs() * 3.0).to(torch.bfloat16)
+    k = (-(k.float().abs()) * 3.0).to(torch.bfloat16)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    for h in range(2):
+        ref = gu.oracle_rows(w, q, k, v, 0, h, None)
+        gu.assert_parity(out[0, h], ref, "negscores h%d" % h)
+
+
 @pytest.mark.parametrize("tile,grid", [((6, 8, 8), (6, 16, 32)), ((2, 8, 8), (4, 16, 16)), ((1, 8, 8), (1, 16, 16))])
 def test_forward_is_bit_reproducible(tile, grid):
     """The same call twice gives the same bits (a vector read of a matrix-instruction result issued too
