@@ -165,17 +165,21 @@ def load_mfma_probe():
     if not os.path.exists(path):
         raise RuntimeError("%s is not built: run `python -m paper_2502_04507_amd.build_lib`" % path)
     lib = ctypes.CDLL(path)
-    lib.mfma_probe.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
-    lib.mfma_probe.restype = ctypes.c_int
+    for fn in (lib.mfma_probe, lib.mfma_probe_16x16x32):
+        fn.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        fn.restype = ctypes.c_int
 
-    def run(operands, iters, workgroups, sink):
+    def run(operands, iters, workgroups, sink, shape="32x32x16"):
+        """Launches one probe; returns the flops it executes.  32x32x16: 4 waves per workgroup, 16 instructions of
+        32768 flop per round; 16x16x32: 12 waves per workgroup, 32 instructions of 16384 flop per round."""
+        waves = 4 if shape == "32x32x16" else 12
         assert operands.dtype == torch.bfloat16 and operands.numel() >= 8192 and operands.is_contiguous()
-        assert sink.dtype == torch.float32 and sink.numel() >= workgroups * 256
-        rc = lib.mfma_probe(operands.data_ptr(), iters, workgroups, sink.data_ptr(),
-                            torch.cuda.current_stream().cuda_stream)
+        assert sink.dtype == torch.float32 and sink.numel() >= workgroups * waves * 64
+        fn = lib.mfma_probe if shape == "32x32x16" else lib.mfma_probe_16x16x32
+        rc = fn(operands.data_ptr(), iters, workgroups, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
         if rc != 0:
             raise RuntimeError("mfma_probe failed with status %d" % rc)
-        return float(workgroups) * 4 * iters * 16 * 32768
+        return float(workgroups) * waves * iters * 16 * 32768
     return run
 
 
@@ -483,9 +487,17 @@ def main():
         probe_flops = mfma_probe(operands, 10000, 512, sink)
         probe_ms = event_time_ms(lambda: mfma_probe(operands, 10000, 512, sink), 5)
         probe[label + "_tflops"] = probe_flops / (probe_ms * 1e-3) / 1e12
-    probe["sta_forward_frac_of_random_operand_rate"] = fwd_tflops / probe["random_operands_tflops"]
-    probe["what"] = ("v_mfma_f32_32x32x16_bf16 only, 2 waves per SIMD on all CUs, no memory traffic; the nominal "
-                     "peak in `roofline` assumes 2.4 GHz, which the chip does not hold on random data")
+        # the forward kernel's own instruction, order and occupancy: one workgroup of 12 waves per CU
+        sink3 = torch.empty(256 * 768, dtype=torch.float32, device=device)
+        probe_flops = mfma_probe(operands, 5000, 256, sink3, "16x16x32")
+        probe_ms = event_time_ms(lambda: mfma_probe(operands, 5000, 256, sink3, "16x16x32"), 5)
+        probe["forward_shape_" + label + "_tflops"] = probe_flops / (probe_ms * 1e-3) / 1e12
+    probe["sta_forward_frac_of_random_operand_rate"] = fwd_tflops / probe["forward_shape_random_operands_tflops"]
+    probe["what"] = ("matrix instructions only, all CUs, no memory traffic.  forward_shape_*: v_mfma_f32_16x16x32_bf16 "
+                     "in the order and at the occupancy of the head dimension 128 forward kernel (3 waves per SIMD), "
+                     "which sta_forward_frac_of_random_operand_rate refers to; the other two: v_mfma_f32_32x32x16_bf16 "
+                     "at 2 waves per SIMD (head dimension 64 and gradient kernels).  The nominal peak in `roofline` "
+                     "assumes 2.4 GHz, which the chip does not hold on random data")
     out["mfma_probe"] = probe
 
     if not args.no_backward and w.D == 128 and w.P % 128 == 0:
