@@ -117,7 +117,7 @@ int sta_forward_lse(const void *q_tiled, const void *k_tiled, const void *v_tile
  * scores and lse in fp32, P and dS are rounded to bf16 for the matrix products, accumulation in
  * fp32, results rounded to bf16.  No atomics: repeated calls give identical bits.
  * workspace: device, 16-byte aligned, at least sta_backward_workspace_bytes(B, H, grid) bytes
- * (one float per query row), else STA_ERR_WORKSPACE.  lse_tiled must be 16-byte aligned as well
+ * (two floats per query row), else STA_ERR_WORKSPACE.  lse_tiled must be 16-byte aligned as well
  * (the kernels read it four rows at a time), else STA_ERR_SHAPE.
  * Supported: D in {64, 128}; P a multiple of 32 (D = 128 with P a multiple of 128 takes the fast
  * kernels, everything else simple one-wave kernels); anything else returns STA_ERR_UNSUPPORTED.

@@ -437,7 +437,7 @@ int sta_query_tile_box(const int grid_tiles[3], const int window_tiles[3], const
 size_t sta_backward_workspace_bytes(int B, int H, const int grid[3])
 {
     if (!grid || B <= 0 || H <= 0 || grid[0] <= 0 || grid[1] <= 0 || grid[2] <= 0) return 0;
-    return (size_t)B * H * (size_t)grid[0] * grid[1] * grid[2] * sizeof(float);
+    return 2 * (size_t)B * H * (size_t)grid[0] * grid[1] * grid[2] * sizeof(float);     // two row statistics
 }
 
 int sta_backward(const void *q_tiled, const void *k_tiled, const void *v_tiled, const void *o_tiled,
@@ -454,7 +454,8 @@ int sta_backward(const void *q_tiled, const void *k_tiled, const void *v_tiled, 
     if (!sta::backward_supported((int)s.P, D)) return STA_ERR_UNSUPPORTED;
     const size_t bytes = (size_t)B * H * s.N * D * 2;
     const size_t stat_bytes = (size_t)B * H * s.N * sizeof(float);
-    if (!workspace || workspace_bytes < stat_bytes || ((uintptr_t)workspace & 15) != 0) return STA_ERR_WORKSPACE;
+    const size_t ws_bytes = 2 * stat_bytes;
+    if (!workspace || workspace_bytes < ws_bytes || ((uintptr_t)workspace & 15) != 0) return STA_ERR_WORKSPACE;
     if (((uintptr_t)lse_tiled & 15) != 0) return STA_ERR_SHAPE;
     const void *inputs[5] = {q_tiled, k_tiled, v_tiled, o_tiled, d_o_tiled};
     void *outputs[3] = {d_q_tiled, d_k_tiled, d_v_tiled};
@@ -463,12 +464,12 @@ int sta_backward(const void *q_tiled, const void *k_tiled, const void *v_tiled, 
             if (ranges_overlap(outputs[i], bytes, inputs[j], bytes)) return STA_ERR_ALIAS;
         for (int j = i + 1; j < 3; ++j)
             if (ranges_overlap(outputs[i], bytes, outputs[j], bytes)) return STA_ERR_ALIAS;
-        if (ranges_overlap(outputs[i], bytes, lse_tiled, stat_bytes) || ranges_overlap(outputs[i], bytes, workspace, stat_bytes))
+        if (ranges_overlap(outputs[i], bytes, lse_tiled, stat_bytes) || ranges_overlap(outputs[i], bytes, workspace, ws_bytes))
             return STA_ERR_ALIAS;
     }
     for (int j = 0; j < 5; ++j)
-        if (ranges_overlap(workspace, stat_bytes, inputs[j], bytes)) return STA_ERR_ALIAS;
-    if (ranges_overlap(workspace, stat_bytes, lse_tiled, stat_bytes)) return STA_ERR_ALIAS;
+        if (ranges_overlap(workspace, ws_bytes, inputs[j], bytes)) return STA_ERR_ALIAS;
+    if (ranges_overlap(workspace, ws_bytes, lse_tiled, stat_bytes)) return STA_ERR_ALIAS;
     if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
     sta::FwdParams p = make_fwd_params(s, H, scale * 1.4426950408889634f);
 

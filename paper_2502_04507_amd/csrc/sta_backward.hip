@@ -68,15 +68,14 @@ __device__ __forceinline__ void tr_issue(shortx4 (&frag)[4][2], const uint32_t (
     });
 }
 
-// acc(32 x 32) = A B with A = a staged sub-block read by rows (A rows = its 32 tokens, k = channels) at byte
+// acc(32 x 32) = init + A B with A = a staged sub-block read by rows (A rows = its 32 tokens, k = channels) at byte
 // offset OFF of LDS, and B = eight resident fragments (k = channels).  Reads go out one group of four k-steps
 // ahead of the MFMAs that use them.
 template <int OFF>
-__device__ __forceinline__ floatx16 rows_times_resident(const uint32_t (&row_addr)[8], const bf16x8 (&resident)[8])
+__device__ __forceinline__ floatx16 rows_times_resident(const uint32_t (&row_addr)[8], const bf16x8 (&resident)[8],
+                                                        const floatx16 &init)
 {
-    floatx16 acc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    floatx16 acc = init;
     bf16x8 frag[2][4];
     k_issue<0, kRowB, OFF>(frag[0], row_addr);
     k_issue<1, kRowB, OFF>(frag[1], row_addr);
@@ -236,10 +235,15 @@ __device__ __forceinline__ void store_columns(bf16_raw *dst, int lane, const flo
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// delta_i = dO_i . O_i, one 16-lane group per row (each lane 16 bytes of the 256-byte row).
+// Row statistics in the form the two kernels below start their accumulators with: neg_delta_i = -(dO_i . O_i)
+// and neg_lse_i = -lse_i / scale, so that the matrix instructions deliver dP - delta and S - lse / scale and
+// neither a subtraction nor a fused multiply-add per element is left (P = 2^(scale * log2(e) * (S - lse / scale))).
+// One 16-lane group per row (each lane 16 bytes of the 256-byte row).
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void sta_bwd_delta_kernel(const uint4 *__restrict__ o, const uint4 *__restrict__ d_o,
-                                                            float *__restrict__ delta, size_t rows)
+                                                            const float *__restrict__ lse, float inv_scale,
+                                                            float *__restrict__ neg_delta, float *__restrict__ neg_lse,
+                                                            size_t rows)
 {
     const size_t row = (size_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int part = threadIdx.x & 15;
@@ -255,7 +259,10 @@ __global__ __launch_bounds__(256) void sta_bwd_delta_kernel(const uint4 *__restr
     }
 #pragma unroll
     for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 16);
-    if (row < rows && part == 0) delta[row] = acc;
+    if (row < rows && part == 0) {
+        neg_delta[row] = -acc;
+        neg_lse[row] = -lse[row] * inv_scale;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -266,8 +273,8 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
                                                                  const bf16_raw *__restrict__ k,
                                                                  const bf16_raw *__restrict__ v,
                                                                  const bf16_raw *__restrict__ d_o,
-                                                                 const float *__restrict__ lse,
-                                                                 const float *__restrict__ delta,
+                                                                 const float *__restrict__ neg_lse,
+                                                                 const float *__restrict__ neg_delta,
                                                                  bf16_raw *__restrict__ d_q, sta::FwdParams p,
                                                                  sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
 {
@@ -315,8 +322,16 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
     load_resident(q + my_row * kD, lane, Qr);
     load_resident(d_o + my_row * kD, lane, Gr);
     const float c = p.scale_log2e;
-    const float lse2 = lse[my_row + lo] * kLog2e;
-    const float dl = delta[my_row + lo];
+    // a lane owns one query column: its 16 accumulator registers all start at that query's statistic
+    floatx16 s_init, dp_init;
+    {
+        const float a = neg_lse[my_row + lo], b = neg_delta[my_row + lo];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            s_init[r] = a;
+            dp_init[r] = b;
+        }
+    }
 
     floatx16 dQ[4];
 #pragma unroll
@@ -346,15 +361,15 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
         else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         __syncthreads();
         issue_next();
-        const floatx16 S = rows_times_resident<ST + K_TILE>(row_addr, Qr);     // S^T  = K Q^T   (keys x queries)
-        const floatx16 dP = rows_times_resident<ST + V_TILE>(row_addr, Gr);    // dP^T = V dO^T
+        const floatx16 S = rows_times_resident<ST + K_TILE>(row_addr, Qr, s_init);     // K Q^T - lse / scale
+        const floatx16 dP = rows_times_resident<ST + V_TILE>(row_addr, Gr, dp_init);   // V dO^T - delta
         TransposedProduct<ST + K_TILE> k_t;
         k_t.prefetch(tr_addr);
         float ds[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float prob = __builtin_amdgcn_exp2f(fmaf(S[r], c, -lse2));
-            ds[r] = prob * (dP[r] - dl);
+            const float prob = __builtin_amdgcn_exp2f(S[r] * c);
+            ds[r] = prob * dP[r];
         }
         bf16x8 dSb[2];
         pack16(ds, dSb);
@@ -385,8 +400,8 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
                                                              const bf16_raw *__restrict__ k,
                                                              const bf16_raw *__restrict__ v,
                                                              const bf16_raw *__restrict__ d_o,
-                                                             const float *__restrict__ lse,
-                                                             const float *__restrict__ delta,
+                                                             const float *__restrict__ neg_lse,
+                                                             const float *__restrict__ neg_delta,
                                                              bf16_raw *__restrict__ d_k,
                                                              bf16_raw *__restrict__ d_v, sta::FwdParams p,
                                                              sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
@@ -420,11 +435,11 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
     // DMA: each operand is 8 instructions of 1 KB (4 rows); wave w issues instruction w of each.
     const int dma_row = 4 * wave + (lane >> 4);
     const uint32_t src_off = src_chunk_offset(dma_row, lane & 15);
-    // Row statistics of the staged sub-block (lse for the first role, delta for the second) travel with it: one
+    // Row statistics of the staged sub-block (-lse / scale for the first role, -delta for the second) travel with it: one
     // 4-byte-per-lane DMA instruction of the last wave brings the 32 + 32 floats into LDS, and every wave reads the
     // rows 8*g + 4*hb + t its accumulator registers belong to from there.  (Loading them from global memory into
     // registers in every wave, 32 wide loads per sub-block and CU, cost 2 ms of the launch.)
-    const float *stat_src = (lane < kSub ? lse : delta) + head_row + (lane & (kSub - 1));
+    const float *stat_src = (lane < kSub ? neg_lse : neg_delta) + head_row + (lane & (kSub - 1));
     auto issue_loads = [&](int stage, uint32_t first_row) {
         const size_t base = (size_t)first_row * kRowB;
         char *dst = smem + stage * STAGE_B + wave * 1024;
@@ -470,7 +485,7 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();       // the stage is complete; the other stage and the exchange buffer are free
         issue_next();
-        float st[16];
+        floatx16 st;           // the accumulators of the first product start at the statistics of their rows
         {
             const char *stats = smem + STATS + decltype(stage_c)::value * STAT_B + (probs_role ? 0 : kSub * 4) + 16 * hb;
 #pragma unroll
@@ -482,12 +497,12 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
         }
         floatx16 X;
         if (probs_role) {
-            X = rows_times_resident<ST + Q_TILE>(row_addr, resident);           // S = Q K^T (queries x keys)
+            X = rows_times_resident<ST + Q_TILE>(row_addr, resident, st);       // Q K^T - lse / scale (queries x keys)
             TransposedProduct<ST + G_TILE> g_t;
             g_t.prefetch(tr_addr);
             float prob[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) prob[r] = __builtin_amdgcn_exp2f(fmaf(X[r], c, -st[r] * kLog2e));
+            for (int r = 0; r < 16; ++r) prob[r] = __builtin_amdgcn_exp2f(X[r] * c);
             bf16x8 Pb[2];
             pack16(prob, Pb);
             lds_write_b128(xchg_addr, Pb[0]);
@@ -496,7 +511,7 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
             __builtin_amdgcn_s_barrier();
             g_t.run(tr_addr, Pb, acc);                                          // dV^T += dO^T P
         } else {
-            X = rows_times_resident<ST + G_TILE>(row_addr, resident);           // dP = dO V^T
+            X = rows_times_resident<ST + G_TILE>(row_addr, resident, st);       // dO V^T - delta
             TransposedProduct<ST + Q_TILE> q_t;
             q_t.prefetch(tr_addr);
             __builtin_amdgcn_s_barrier();
@@ -508,7 +523,7 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) ds[8 * j + e] = static_cast<float>(Pb[j][e]) * (X[8 * j + e] - st[8 * j + e]);
+                for (int e = 0; e < 8; ++e) ds[8 * j + e] = static_cast<float>(Pb[j][e]) * X[8 * j + e];
             bf16x8 dSb[2];
             pack16(ds, dSb);
             q_t.run(tr_addr, dSb, acc);                                         // dK^T += Q^T dS
@@ -801,10 +816,13 @@ hipError_t launch_backward(const void *q, const void *k, const void *v, const vo
         return launch_backward_generic<64>(qq, kk, vv, o, d_o, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream);
     if (p.P % kCols != 0)
         return launch_backward_generic<128>(qq, kk, vv, o, d_o, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream);
+    // the workspace holds two floats per row here: -delta, then -lse / scale
+    const size_t rows = (size_t)B * p.H * p.N;       // all heads of the tensor at once
+    float *neg_delta = delta, *neg_lse = delta + rows;
     if (compute_delta) {
-        const size_t rows = (size_t)B * p.H * p.N;   // all heads of the tensor at once
         sta_bwd_delta_kernel<<<dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, stream>>>(
-            static_cast<const uint4 *>(o), static_cast<const uint4 *>(d_o), delta, rows);
+            static_cast<const uint4 *>(o), static_cast<const uint4 *>(d_o), lse, kLog2e / p.scale_log2e, neg_delta, neg_lse,
+            rows);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -816,10 +834,10 @@ hipError_t launch_backward(const void *q, const void *k, const void *v, const vo
     // 18.5, 18.5, 19.3 ms.
     const uint32_t chunk = p.n_w * (p.P / kCols);
     dim3 block(kNW * 64);
-    sta_bwd_dq_kernel<2><<<grid_for(chunk), block, 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_q), p, win, n_bh, chunk);
+    sta_bwd_dq_kernel<2><<<grid_for(chunk), block, 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_q), p, win, n_bh, chunk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    sta_bwd_dkv_kernel<<<grid_for(chunk), dim3(512), 0, stream>>>(qq, kk, vv, gg, lse, delta, static_cast<bf16_raw *>(d_k),
+    sta_bwd_dkv_kernel<<<grid_for(chunk), dim3(512), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_k),
                                                    static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk);
     return hipGetLastError();
 }

@@ -205,9 +205,11 @@ def test_backward_errors():
     t = lambda: torch.zeros((1, 1, w.N, 128), dtype=torch.bfloat16, device=DEV)
     qt, kt, vt, ot, gt, dq, dk, dv = (t() for _ in range(8))
     lse = torch.zeros((1, 1, w.N), dtype=torch.float32, device=DEV)
-    ws = torch.zeros(w.N, dtype=torch.float32, device=DEV)
+    need = sta.sta_backward_workspace_bytes(1, 1, w.grid)
+    assert need >= w.N * 4
+    ws = torch.zeros(need // 4, dtype=torch.float32, device=DEV)
     with pytest.raises(sta.StaError) as e:       # workspace too small
-        sta.sta_backward(qt, kt, vt, ot, gt, lse, dq, dk, dv, w.grid, w.tile, w.window_tiles, ws[: w.N // 2])
+        sta.sta_backward(qt, kt, vt, ot, gt, lse, dq, dk, dv, w.grid, w.tile, w.window_tiles, ws[: need // 4 - 4])
     assert e.value.status == 6
     with pytest.raises(sta.StaError) as e:       # output aliases an input
         sta.sta_backward(qt, kt, vt, ot, gt, lse, qt, dk, dv, w.grid, w.tile, w.window_tiles, ws)
