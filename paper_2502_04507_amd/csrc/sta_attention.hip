@@ -779,8 +779,9 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_
 // The same kernel built on v_mfma_f32_16x16x32_bf16 (head dimension 128, 32-key sub-blocks).  On this chip the run
 // time on real data follows the energy of the instruction stream (the package sits at its power limit and lowers
 // the clock), and the 16x16x32 shape is the cheaper one per flop: it reads and writes 4 accumulator registers per
-// 16 Kflop where 32x32x16 moves 16 per 32 Kflop.  Measured with nothing but matrix instructions on N(0,1) operands,
-// two waves per SIMD: 2019 TFLOP/s against 1784 (equal, 2440, on constant operands).
+// 16 Kflop where 32x32x16 moves 16 per 32 Kflop.  Measured with nothing but matrix instructions on N(0,1) operands:
+// 1969 TFLOP/s against 1783 at two waves per SIMD (both 2440-2450 on constant operands), 1901 against 1443 at the
+// three waves per SIMD this kernel runs with (2412 against 1839 on constant operands).
 // Layout: a lane holds column c16 = lane & 15 of a 16x16 result (a query) and rows 4*g4 .. 4*g4+3 (g4 = lane >> 4);
 // of an operand it holds row/column c16 and the k-chunk 8*g4 .. 8*g4+7.  A wave's 32 queries are two query blocks;
 // every K and V fragment read from LDS feeds both.
@@ -1017,7 +1018,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
     // (lds_off: where the stage begins; it enters the operand base addresses at run time)
     // units of the accumulated scores: base-2 exponents if Q was scaled, raw dot products otherwise
     const float c = PRESCALE ? 1.f : p.scale_log2e;
-    auto half_block = [&](uint32_t lds_off, float grow_above) {
+    auto sub_block_at = [&](uint32_t lds_off, float grow_above) {
         const uint32_t kb_ = k_base + lds_off;
         uint32_t vb_[4];
 #pragma unroll
@@ -1174,7 +1175,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
         __syncthreads();   // ... and everyone's; the stage read in the previous iteration is free again
         issue_next();      // refills stage (iter - 1) % STAGES
         // growth threshold: 2^8 in the units of the scores, -infinity for the first keys of an item
-        half_block((uint32_t)((iter & 1) * STAGE_BYTES), __uint_as_float(iter == 0 ? 0xff800000u : bound_bits));
+        sub_block_at((uint32_t)((iter & 1) * STAGE_BYTES), __uint_as_float(iter == 0 ? 0xff800000u : bound_bits));
     }
 
     // ---- finalize -------------------------------------------------------------------
