@@ -539,6 +539,304 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
 
 
 // ---------------------------------------------------------------------------------------------------------
+// dK, dV on v_mfma_f32_16x16x32_bf16.  One workgroup of 2 * NPAIR waves per 32 * NPAIR keys; the same split of the
+// four products over pairs of waves as above, in the forward kernel's register layout: a lane holds key column
+// c16 = lane & 15 of a 16x16 result and the query rows 4*g4 .. 4*g4+3 (g4 = lane >> 4); a wave's 32 keys are two
+// key blocks, and every fragment read from LDS feeds both.  Per wave and 32-query sub-block: 32 matrix
+// instructions, 40 vector instructions, 26 LDS reads, in 168 registers, so that three waves per SIMD fit (six
+// pairs: 192 keys per workgroup, every staged Q / dO sub-block serves 1.5 times the columns it served above).
+// LDS layout of a staged operand: groups of 4 rows (1 KB, one DMA instruction), kStagedGroup = 1024 + 32 bytes
+// apart, chunk c of row j of a group at c ^ (j << 2).  It serves both ways of reading without bank conflicts:
+//  - by rows (16-byte reads, served for lanes 0-7 together with 24-31, i.e. rows 0..7 at chunk x with rows 8..15
+//    at chunk x ^ 1): the four rows of a group land in the four quarters of the 256 bytes, and consecutive groups
+//    are turned by 32 bytes, which together with the odd chunk of the second half covers all sixteen positions;
+//  - transposed (8-byte reads, served 32 lanes at a time: 8 consecutive rows, two neighbouring chunks each).
+// The stage, the operand, the query block of a row read and the odd channel blocks of a transposing read are
+// offsets inside the instructions: a wave keeps four row addresses (one per k-step) and four transposing ones.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kStagedGroup = 1024 + 32;
+constexpr int kStagedTile = (kSub / 4) * kStagedGroup;      // one staged operand of 32 rows
+
+// X[qb][kb] (16 queries x 16 keys) = init[qb] + A B: A = the staged operand at byte offset OFF read by rows
+// (A rows = queries, k = channels), B = resident fragments of the wave's 32 columns.  Four reads in flight; a
+// fragment feeds both key blocks, taken 0, 1, 1, 0, .. so that one operand changes from one matrix instruction
+// to the next.
+template <int OFF>
+__device__ __forceinline__ void staged_rows_times_resident(const uint32_t (&row_addr)[4], const bf16x8 (&resident)[2][4],
+                                                           const floatx4 (&init)[2], floatx4 (&X)[2][2])
+{
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) X[qb][kb] = init[qb];
+    constexpr int QB1 = OFF + 4 * kStagedGroup;                 // rows 16..31
+    bf16x8 a0 = ds_read_b128_at<OFF>(row_addr[0]), a1 = ds_read_b128_at<OFF>(row_addr[1]);
+    bf16x8 a2 = ds_read_b128_at<OFF>(row_addr[2]), a3 = ds_read_b128_at<OFF>(row_addr[3]);
+    lds_wait2<2>(a0, a1);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) X[0][kb] = mfma_16x16x32(a0, resident[kb][0], X[0][kb]);
+#pragma unroll
+    for (int kb = 1; kb >= 0; --kb) X[0][kb] = mfma_16x16x32(a1, resident[kb][1], X[0][kb]);
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 b0 = ds_read_b128_at<QB1>(row_addr[0]), b1 = ds_read_b128_at<QB1>(row_addr[1]);
+    lds_wait2<2>(a2, a3);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) X[0][kb] = mfma_16x16x32(a2, resident[kb][2], X[0][kb]);
+#pragma unroll
+    for (int kb = 1; kb >= 0; --kb) X[0][kb] = mfma_16x16x32(a3, resident[kb][3], X[0][kb]);
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 b2 = ds_read_b128_at<QB1>(row_addr[2]), b3 = ds_read_b128_at<QB1>(row_addr[3]);
+    lds_wait2<2>(b0, b1);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) X[1][kb] = mfma_16x16x32(b0, resident[kb][0], X[1][kb]);
+#pragma unroll
+    for (int kb = 1; kb >= 0; --kb) X[1][kb] = mfma_16x16x32(b1, resident[kb][1], X[1][kb]);
+    __builtin_amdgcn_sched_barrier(0);
+    lds_wait2<0>(b2, b3);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) X[1][kb] = mfma_16x16x32(b2, resident[kb][2], X[1][kb]);
+#pragma unroll
+    for (int kb = 1; kb >= 0; --kb) X[1][kb] = mfma_16x16x32(b3, resident[kb][3], X[1][kb]);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// acc[cb][kb] (16 channels x 16 keys) += A B: A = the staged operand at OFF read transposed (A rows = channels,
+// k = its 32 queries: index 8*g4 + i is query 4*g4 + i of the first 16 for i < 4, of the second 16 otherwise),
+// B = packed[kb].  The reads of channel blocks 0..3 can go out before B exists.
+template <int OFF>
+struct StagedTransposedProduct {
+    shortx4 frag[2][4][2];
+    template <int G>
+    __device__ __forceinline__ void issue(const uint32_t (&tr_addr)[4])
+    {
+        static_for<0, 4>([&](auto i) {
+            constexpr int cb = 4 * G + decltype(i)::value;
+            frag[G][cb & 3][0] = ds_read_tr16<OFF + (cb & 1) * 32>(tr_addr[cb >> 1]);
+            frag[G][cb & 3][1] = ds_read_tr16<OFF + (cb & 1) * 32 + 4 * kStagedGroup>(tr_addr[cb >> 1]);
+        });
+    }
+    __device__ __forceinline__ void prefetch(const uint32_t (&tr_addr)[4]) { issue<0>(tr_addr); }
+    __device__ __forceinline__ void run(const uint32_t (&tr_addr)[4], const bf16x8 (&packed)[2], floatx4 (&acc)[8][2])
+    {
+        typedef short shortx8 __attribute__((ext_vector_type(8)));
+        static_for<0, 2>([&](auto gi) {
+            constexpr int g = decltype(gi)::value;
+            if constexpr (g == 0) {
+                issue<1>(tr_addr);
+                pv_wait<8>(frag[0]);
+            } else {
+                pv_wait<0>(frag[1]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const shortx8 a = __builtin_shufflevector(frag[g][i][0], frag[g][i][1], 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int kb = (i & 1) ^ t;
+                    acc[4 * g + i][kb] = mfma_16x16x32(__builtin_bit_cast(bf16x8, a), packed[kb], acc[4 * g + i][kb]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+};
+
+template <int NPAIR>
+__global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_x32_kernel(const bf16_raw *__restrict__ q,
+                                                                         const bf16_raw *__restrict__ k,
+                                                                         const bf16_raw *__restrict__ v,
+                                                                         const bf16_raw *__restrict__ d_o,
+                                                                         const float *__restrict__ neg_lse,
+                                                                         const float *__restrict__ neg_delta,
+                                                                         bf16_raw *__restrict__ d_k,
+                                                                         bf16_raw *__restrict__ d_v, sta::FwdParams p,
+                                                                         sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
+{
+    constexpr int COLS = NPAIR * 32;                    // keys per workgroup
+    constexpr int STAGE_B = 2 * kStagedTile;
+    constexpr int Q_TILE = 0, G_TILE = kStagedTile;
+    constexpr int P_XCHG = 2 * STAGE_B;                 // per pair: 2 key blocks x 64 lanes x 16 B
+    constexpr int STATS = P_XCHG + NPAIR * 2048;        // per stage: -lse / scale then -delta of the 32 staged query rows
+    constexpr int STAT_B = 2 * kSub * 4;
+    constexpr int DMA_WAVES = kSub / 4;                 // one DMA instruction per operand and loading wave
+    constexpr int STAT_WAVE = 2 * NPAIR > DMA_WAVES ? DMA_WAVES : DMA_WAVES - 1;   // a wave of its own where there is one
+    __shared__ __attribute__((aligned(1024))) char smem[STATS + 2 * STAT_B];
+
+    uint32_t kblock, bh_rank;
+    if (!work_item(chunk, p.N / COLS, n_bh, &kblock, &bh_rank)) return;
+    const uint32_t heads = p.heads;
+    const uint32_t h_local = bh_rank % heads, b = bh_rank / heads;
+    const size_t bh = (size_t)b * p.H + p.head_base + h_local;
+    const uint32_t k_tile = (kblock * COLS) / p.P;
+    const StaBox box = sta_query_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1],
+                                             win.w[h_local][2], k_tile);
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, c16 = lane & 15, g4 = lane >> 4;
+    const bool probs_role = wave < NPAIR;               // S, P, dV; the other role: dP, dS, dK
+    const int pair = probs_role ? wave : wave - NPAIR;
+
+    const size_t head_row = bh * p.N;
+    const size_t my_row = head_row + (size_t)kblock * COLS + (size_t)pair * 32;
+    const char *qh = reinterpret_cast<const char *>(q + head_row * kD);
+    const char *gh = reinterpret_cast<const char *>(d_o + head_row * kD);
+
+    // DMA: each operand is 8 instructions of 1 KB (a group of 4 rows); wave w < 8 issues instruction w of each.  The
+    // lane's slot in LDS is fixed (16 * lane), so it fetches the chunk that belongs there.  Wave 8 brings the row
+    // statistics of the sub-block (32 + 32 floats) with one 4-byte-per-lane instruction (wave 7 where there are eight).
+    const uint32_t src_lane_off = (uint32_t)(g4 * kRowB + ((c16 ^ (g4 << 2)) << 4));
+    const uint32_t stat_lane_off = (uint32_t)((lane & (kSub - 1)) * 4);
+    const char *stat_base = reinterpret_cast<const char *>((lane < kSub ? neg_lse : neg_delta) + head_row);
+    auto issue_loads = [&](int stage, uint32_t first_row) {
+        uint32_t off = src_lane_off, soff = stat_lane_off;
+        asm volatile("" : "+v"(off), "+v"(soff));       // keep the lane offsets 32-bit next to a scalar base
+        if (wave < DMA_WAVES) {
+            const size_t base = (size_t)(first_row + 4 * wave) * kRowB;
+            char *dst = smem + stage * STAGE_B + wave * kStagedGroup;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off),
+                                             STA_LDS_PTR(dst + Q_TILE), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off),
+                                             STA_LDS_PTR(dst + G_TILE), 16, 0, 0);
+        }
+        if (wave == STAT_WAVE)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(stat_base + (size_t)first_row * 4 + soff),
+                STA_LDS_PTR(smem + STATS + stage * STAT_B), 4, 0, 0);
+    };
+
+    // Per-lane constants of the operand reads, relative to the start of a staged operand.
+    //  Row reads (A = 16 queries x 32 channels): row c16 = row c16 & 3 of group c16 >> 2, logical chunk 4*ks + g4.
+    //  Transposing reads (A = 16 channels x 32 queries): within each block of 16 lanes, lane 4*j4 + s4 supplies
+    //  channels 4*s4 .. 4*s4+3 of the block's 16 of query row 4*g4 + j4 = row j4 of group g4; logical chunk
+    //  2*cb + (s4 >> 1), one address per value of cb >> 1.
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
+    uint32_t row_addr[4], tr_addr[4];
+    {
+        const int j = c16 & 3, j4 = c16 >> 2, s4 = lane & 3;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            row_addr[ks] = smem_addr + (uint32_t)((c16 >> 2) * kStagedGroup + j * kRowB + ((((ks ^ j) << 2) | g4) << 4));
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+            tr_addr[m] = smem_addr + (uint32_t)(g4 * kStagedGroup + j4 * kRowB + ((((m ^ j4) << 2) | (s4 >> 1)) << 4) + 8 * (s4 & 1));
+    }
+    const uint32_t xchg_addr = smem_addr + P_XCHG + pair * 2048 + lane * 16;   // two planes of 1 KB per pair
+    const uint32_t stat_addr = smem_addr + STATS + (probs_role ? 0 : kSub * 4) + 16 * g4;
+
+    // resident B fragments: K rows (first role) or V rows (second role) of key 16*kb + c16, channels 32*ks + 8*g4 ..
+    bf16x8 resident[2][4];
+    {
+        const bf16_raw *rows = (probs_role ? k : v) + my_row * kD;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                resident[kb][ks] = *reinterpret_cast<const bf16x8 *>(rows + (size_t)(16 * kb + c16) * kD + ks * 32 + g4 * 8);
+    }
+    const float c = p.scale_log2e;
+
+    floatx4 acc[8][2];                                  // dV^T (first role) or dK^T (second role): [channel block][key block]
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) acc[cb][kb] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    BoxWalk walk;
+    walk.start(box, p.n_h, p.n_w, p.P);
+    const int n_iter = box.count() * walk.sub_per_tile;
+    int issued = 0;
+    auto issue_next = [&]() {
+        if (issued < n_iter) {
+            issue_loads(issued & 1, walk.next_row);
+            walk.advance();
+            ++issued;
+        }
+    };
+    issue_next();
+
+    // One sub-block in one role.  (The role is a compile-time argument and each role has its own loop: with the
+    // branch inside a common loop the register allocator serves both paths at once and spills.)
+    auto sub_block = [&](auto role_c, auto stage_c) {
+        constexpr bool PROBS = decltype(role_c)::value;
+        constexpr int ST = decltype(stage_c)::value * STAGE_B;
+        constexpr int ST_STATS = decltype(stage_c)::value * STAT_B;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();       // the stage is complete; the other stage and the exchange buffer are free
+        issue_next();
+        // the accumulators of the first product start at the statistics of their query rows 16*qb + 4*g4 ..
+        floatx4 init[2];
+        {
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            u32x4 r0, r1;
+            asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(r0), "=&v"(r1)
+                         : "v"(stat_addr), "n"(ST_STATS), "n"(ST_STATS + 64));
+            init[0] = __builtin_bit_cast(floatx4, r0);
+            init[1] = __builtin_bit_cast(floatx4, r1);
+        }
+        floatx4 X[2][2];
+        if constexpr (PROBS) {
+            staged_rows_times_resident<ST + Q_TILE>(row_addr, resident, init, X);   // Q K^T - lse / scale
+            StagedTransposedProduct<ST + G_TILE> g_t;
+            g_t.prefetch(tr_addr);
+            __builtin_amdgcn_sched_barrier(0);
+            bf16x8 Pb[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        Pb[kb][4 * qb + e] = static_cast<__bf16>(__builtin_amdgcn_exp2f(X[qb][kb][e] * c));
+            lds_write_b128(xchg_addr, Pb[0]);
+            lds_write_b128(xchg_addr + 1024, Pb[1]);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            g_t.run(tr_addr, Pb, acc);                                              // dV^T += dO^T P
+        } else {
+            staged_rows_times_resident<ST + G_TILE>(row_addr, resident, init, X);   // dO V^T - delta
+            StagedTransposedProduct<ST + Q_TILE> q_t;
+            q_t.prefetch(tr_addr);
+            __builtin_amdgcn_s_barrier();
+            bf16x8 Pb[2];
+            Pb[0] = ds_read_b128_at<0>(xchg_addr);
+            Pb[1] = ds_read_b128_at<1024>(xchg_addr);
+            lds_wait2<0>(Pb[0], Pb[1]);
+            bf16x8 dSb[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        dSb[kb][4 * qb + e] = static_cast<__bf16>(static_cast<float>(Pb[kb][4 * qb + e]) * X[qb][kb][e]);
+            q_t.run(tr_addr, dSb, acc);                                             // dK^T += Q^T dS
+        }
+    };
+    auto all_sub_blocks = [&](auto role_c) {
+        for (int iter = 0; iter < n_iter; iter += 2) {
+            sub_block(role_c, std::integral_constant<int, 0>{});
+            if (iter + 1 < n_iter) sub_block(role_c, std::integral_constant<int, 1>{});
+        }
+    };
+    if (probs_role) all_sub_blocks(std::true_type{});
+    else all_sub_blocks(std::false_type{});
+    // acc[cb][kb][i] = channel 16*cb + 4*g4 + i of key 16*kb + c16
+    bf16_raw *dst = (probs_role ? d_v : d_k) + my_row * kD;
+    const float mul = probs_role ? 1.0f : c * kLn2;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) {
+            bf16x4 ov;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ov[t] = static_cast<__bf16>(acc[cb][kb][t] * mul);
+            *reinterpret_cast<bf16x4 *>(dst + (size_t)(16 * kb + c16) * kD + 16 * cb + 4 * g4) = ov;
+        }
+}
+
+
+// ---------------------------------------------------------------------------------------------------------
 // General shapes: head dimension 64 or 128, any tile size that is a multiple of 32 tokens.  Same mathematics and
 // the same MFMA formulation (one lane owns one column, P or dS goes from the accumulators into the B operand),
 // kept simple: one wave per workgroup and 32 columns, staged operands copied through registers into a
@@ -837,8 +1135,17 @@ hipError_t launch_backward(const void *q, const void *k, const void *v, const vo
     sta_bwd_dq_kernel<2><<<grid_for(chunk), block, 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_q), p, win, n_bh, chunk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    sta_bwd_dkv_kernel<<<grid_for(chunk), dim3(512), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_k),
-                                                   static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk);
+    if (p.P % 192 == 0) {
+        // 192 keys per workgroup: the chunk is again one row of tiles along w
+        const uint32_t total6 = (p.N / 192) * n_bh, chunk6 = p.n_w * (p.P / 192);
+        const dim3 grid6(8 * chunk6 * ((((total6 + chunk6 - 1) / chunk6) + 7) / 8));
+        sta_bwd_dkv_x32_kernel<6><<<grid6, dim3(768), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_k),
+                                                                  static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk6);
+    } else {
+        sta_bwd_dkv_x32_kernel<4><<<grid_for(chunk), dim3(512), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta,
+                                                                            static_cast<bf16_raw *>(d_k),
+                                                                            static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk);
+    }
     return hipGetLastError();
 }
 
