@@ -557,52 +557,48 @@ __global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__r
 constexpr int kStagedGroup = 1024 + 32;
 constexpr int kStagedTile = (kSub / 4) * kStagedGroup;      // one staged operand of 32 rows
 
-// X[qb][kb] (16 queries x 16 keys) = init[qb] + A B: A = the staged operand at byte offset OFF read by rows
-// (A rows = queries, k = channels), B = resident fragments of the wave's 32 columns.  Four reads in flight; a
-// fragment feeds both key blocks, taken 0, 1, 1, 0, .. so that one operand changes from one matrix instruction
-// to the next.
+// X[rb][cb] (16 staged rows x 16 resident columns) += A B: A = the staged operand at byte offset OFF read by rows
+// (k = channels), B = resident fragments of the wave's 32 columns; the caller has set X to the value the sums start
+// from.  Four reads in flight; a fragment feeds both column blocks, taken 0, 1, 1, 0, .. so that one operand changes
+// from one matrix instruction to the next.
 template <int OFF>
 __device__ __forceinline__ void staged_rows_times_resident(const uint32_t (&row_addr)[4], const bf16x8 (&resident)[2][4],
-                                                           const floatx4 (&init)[2], floatx4 (&X)[2][2])
+                                                           floatx4 (&X)[2][2])
 {
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) X[qb][kb] = init[qb];
-    constexpr int QB1 = OFF + 4 * kStagedGroup;                 // rows 16..31
+    constexpr int ROWS16 = OFF + 4 * kStagedGroup;                 // rows 16..31
     bf16x8 a0 = ds_read_b128_at<OFF>(row_addr[0]), a1 = ds_read_b128_at<OFF>(row_addr[1]);
     bf16x8 a2 = ds_read_b128_at<OFF>(row_addr[2]), a3 = ds_read_b128_at<OFF>(row_addr[3]);
     lds_wait2<2>(a0, a1);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) X[0][kb] = mfma_16x16x32(a0, resident[kb][0], X[0][kb]);
+    for (int col = 0; col < 2; ++col) X[0][col] = mfma_16x16x32(a0, resident[col][0], X[0][col]);
 #pragma unroll
-    for (int kb = 1; kb >= 0; --kb) X[0][kb] = mfma_16x16x32(a1, resident[kb][1], X[0][kb]);
+    for (int col = 1; col >= 0; --col) X[0][col] = mfma_16x16x32(a1, resident[col][1], X[0][col]);
     __builtin_amdgcn_sched_barrier(0);
-    bf16x8 b0 = ds_read_b128_at<QB1>(row_addr[0]), b1 = ds_read_b128_at<QB1>(row_addr[1]);
+    bf16x8 b0 = ds_read_b128_at<ROWS16>(row_addr[0]), b1 = ds_read_b128_at<ROWS16>(row_addr[1]);
     lds_wait2<2>(a2, a3);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) X[0][kb] = mfma_16x16x32(a2, resident[kb][2], X[0][kb]);
+    for (int col = 0; col < 2; ++col) X[0][col] = mfma_16x16x32(a2, resident[col][2], X[0][col]);
 #pragma unroll
-    for (int kb = 1; kb >= 0; --kb) X[0][kb] = mfma_16x16x32(a3, resident[kb][3], X[0][kb]);
+    for (int col = 1; col >= 0; --col) X[0][col] = mfma_16x16x32(a3, resident[col][3], X[0][col]);
     __builtin_amdgcn_sched_barrier(0);
-    bf16x8 b2 = ds_read_b128_at<QB1>(row_addr[2]), b3 = ds_read_b128_at<QB1>(row_addr[3]);
+    bf16x8 b2 = ds_read_b128_at<ROWS16>(row_addr[2]), b3 = ds_read_b128_at<ROWS16>(row_addr[3]);
     lds_wait2<2>(b0, b1);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) X[1][kb] = mfma_16x16x32(b0, resident[kb][0], X[1][kb]);
+    for (int col = 0; col < 2; ++col) X[1][col] = mfma_16x16x32(b0, resident[col][0], X[1][col]);
 #pragma unroll
-    for (int kb = 1; kb >= 0; --kb) X[1][kb] = mfma_16x16x32(b1, resident[kb][1], X[1][kb]);
+    for (int col = 1; col >= 0; --col) X[1][col] = mfma_16x16x32(b1, resident[col][1], X[1][col]);
     __builtin_amdgcn_sched_barrier(0);
     lds_wait2<0>(b2, b3);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) X[1][kb] = mfma_16x16x32(b2, resident[kb][2], X[1][kb]);
+    for (int col = 0; col < 2; ++col) X[1][col] = mfma_16x16x32(b2, resident[col][2], X[1][col]);
 #pragma unroll
-    for (int kb = 1; kb >= 0; --kb) X[1][kb] = mfma_16x16x32(b3, resident[kb][3], X[1][kb]);
+    for (int col = 1; col >= 0; --col) X[1][col] = mfma_16x16x32(b3, resident[col][3], X[1][col]);
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// acc[cb][kb] (16 channels x 16 keys) += A B: A = the staged operand at OFF read transposed (A rows = channels,
-// k = its 32 queries: index 8*g4 + i is query 4*g4 + i of the first 16 for i < 4, of the second 16 otherwise),
-// B = packed[kb].  The reads of channel blocks 0..3 can go out before B exists.
+// acc[cb][col] (16 channels x 16 resident columns) += A B: A = the staged operand at OFF read transposed (A rows =
+// channels, k = its 32 rows: index 8*g4 + i is row 4*g4 + i of the first 16 for i < 4, of the second 16 otherwise),
+// B = packed[col].  The reads of channel blocks 0..3 can go out before B exists.
 template <int OFF>
 struct StagedTransposedProduct {
     shortx4 frag[2][4][2];
@@ -632,14 +628,166 @@ struct StagedTransposedProduct {
                 const shortx8 a = __builtin_shufflevector(frag[g][i][0], frag[g][i][1], 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    const int kb = (i & 1) ^ t;
-                    acc[4 * g + i][kb] = mfma_16x16x32(__builtin_bit_cast(bf16x8, a), packed[kb], acc[4 * g + i][kb]);
+                    const int col = (i & 1) ^ t;
+                    acc[4 * g + i][col] = mfma_16x16x32(__builtin_bit_cast(bf16x8, a), packed[col], acc[4 * g + i][col]);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
         });
     }
 };
+
+// ---------------------------------------------------------------------------------------------------------
+// dQ on v_mfma_f32_16x16x32_bf16.  One workgroup of 4 waves per 128 queries, two workgroups per CU; a lane holds query
+// column c16 of its wave's two 16-query blocks.  LDS stage: K (read by rows and transposed) and V (read by rows), in
+// the layout described above.  Per wave and 32-key sub-block: S^T = K Q^T - lse / scale and dP^T = V dO^T - delta
+// (16 matrix instructions each, the statistics of the lane's query as the initial value), dS^T = 2^(c S^T) o dP^T,
+// dQ^T += K^T dS^T (16).
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_x32_kernel(const bf16_raw *__restrict__ q,
+                                                                     const bf16_raw *__restrict__ k,
+                                                                     const bf16_raw *__restrict__ v,
+                                                                     const bf16_raw *__restrict__ d_o,
+                                                                     const float *__restrict__ neg_lse,
+                                                                     const float *__restrict__ neg_delta,
+                                                                     bf16_raw *__restrict__ d_q, sta::FwdParams p,
+                                                                     sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
+{
+    constexpr int STAGE_B = 2 * kStagedTile;
+    constexpr int K_TILE = 0, V_TILE = kStagedTile;
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
+
+    uint32_t qblock, bh_rank;
+    if (!work_item(chunk, p.N / kCols, n_bh, &qblock, &bh_rank)) return;
+    const uint32_t heads = p.heads;
+    const uint32_t h_local = bh_rank % heads, b = bh_rank / heads;
+    const size_t bh = (size_t)b * p.H + p.head_base + h_local;
+    const uint32_t q_tile = (qblock * kCols) / p.P;
+    const StaBox box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1], win.w[h_local][2],
+                                           q_tile);
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63, c16 = lane & 15, g4 = lane >> 4;
+
+    const size_t my_row = bh * p.N + (size_t)qblock * kCols + (size_t)wave * 32;
+    const char *kh = reinterpret_cast<const char *>(k + bh * p.N * kD);
+    const char *vh = reinterpret_cast<const char *>(v + bh * p.N * kD);
+
+    // DMA: each operand is 8 instructions of 1 KB (a group of 4 rows); wave w issues instructions 2w and 2w+1 of each.
+    const uint32_t src_lane_off = (uint32_t)(g4 * kRowB + ((c16 ^ (g4 << 2)) << 4));
+    auto issue_loads = [&](int stage, uint32_t first_row) {
+        uint32_t off = src_lane_off;
+        asm volatile("" : "+v"(off));                   // keep the lane offset 32-bit next to a scalar base
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int group = 2 * wave + i;
+            const size_t base = (size_t)(first_row + 4 * group) * kRowB;
+            char *dst = smem + stage * STAGE_B + group * kStagedGroup;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + base + off),
+                                             STA_LDS_PTR(dst + K_TILE), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + base + off),
+                                             STA_LDS_PTR(dst + V_TILE), 16, 0, 0);
+        }
+    };
+
+    // per-lane constants of the operand reads (as in the dK/dV kernel, with key rows in the place of query rows)
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
+    uint32_t row_addr[4], tr_addr[4];
+    {
+        const int j = c16 & 3, j4 = c16 >> 2, s4 = lane & 3;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            row_addr[ks] = smem_addr + (uint32_t)((c16 >> 2) * kStagedGroup + j * kRowB + ((((ks ^ j) << 2) | g4) << 4));
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+            tr_addr[m] = smem_addr + (uint32_t)(g4 * kStagedGroup + j4 * kRowB + ((((m ^ j4) << 2) | (s4 >> 1)) << 4) + 8 * (s4 & 1));
+    }
+
+    // resident B fragments: query 16*qb + c16, channels 32*ks + 8*g4 ..
+    bf16x8 Qr[2][4], Gr[2][4];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const size_t at = (my_row + 16 * qb + c16) * kD + ks * 32 + g4 * 8;
+            Qr[qb][ks] = *reinterpret_cast<const bf16x8 *>(q + at);
+            Gr[qb][ks] = *reinterpret_cast<const bf16x8 *>(d_o + at);
+        }
+    const float c = p.scale_log2e;
+    // a lane owns one query column per block: the four registers of an accumulator all start at that query's statistic
+    floatx4 s_init[2], dp_init[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const float a = neg_lse[my_row + 16 * qb + c16], d = neg_delta[my_row + 16 * qb + c16];
+        s_init[qb] = floatx4{a, a, a, a};
+        dp_init[qb] = floatx4{d, d, d, d};
+    }
+
+    floatx4 dQ[8][2];                                   // [channel block][query block]
+#pragma unroll
+    for (int cb = 0; cb < 8; ++cb)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) dQ[cb][qb] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    BoxWalk walk;
+    walk.start(box, p.n_h, p.n_w, p.P);
+    const int n_iter = box.count() * walk.sub_per_tile;
+    int issued = 0;
+    auto issue_next = [&]() {
+        if (issued < n_iter) {
+            issue_loads(issued & 1, walk.next_row);
+            walk.advance();
+            ++issued;
+        }
+    };
+    issue_next();
+
+    auto sub_block = [&](auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value * STAGE_B;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        issue_next();
+        floatx4 S[2][2], dP[2][2];                      // [key block][query block]
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                S[kb][qb] = s_init[qb];
+                dP[kb][qb] = dp_init[qb];
+            }
+        staged_rows_times_resident<ST + K_TILE>(row_addr, Qr, S);       // K Q^T - lse / scale
+        staged_rows_times_resident<ST + V_TILE>(row_addr, Gr, dP);      // V dO^T - delta
+        StagedTransposedProduct<ST + K_TILE> k_t;
+        k_t.prefetch(tr_addr);
+        __builtin_amdgcn_sched_barrier(0);
+        // dS^T, rounded to bf16 and packed as the B operand of the last product: k index 8*g4 + i is key 4*g4 + i
+        // of the first key block (i < 4) or of the second
+        bf16x8 dSb[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    dSb[qb][4 * kb + e] = static_cast<__bf16>(__builtin_amdgcn_exp2f(S[kb][qb][e] * c) * dP[kb][qb][e]);
+        k_t.run(tr_addr, dSb, dQ);                                       // dQ^T += K^T dS^T
+    };
+    for (int iter = 0; iter < n_iter; iter += 2) {
+        sub_block(std::integral_constant<int, 0>{});
+        if (iter + 1 < n_iter) sub_block(std::integral_constant<int, 1>{});
+    }
+    // dQ[cb][qb][i] = channel 16*cb + 4*g4 + i of query 16*qb + c16
+    const float mul = c * kLn2;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int cb = 0; cb < 8; ++cb) {
+            bf16x4 ov;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ov[t] = static_cast<__bf16>(dQ[cb][qb][t] * mul);
+            *reinterpret_cast<bf16x4 *>(d_q + (my_row + 16 * qb + c16) * kD + 16 * cb + 4 * g4) = ov;
+        }
+}
 
 template <int NPAIR>
 __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_x32_kernel(const bf16_raw *__restrict__ q,
@@ -775,8 +923,12 @@ __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_x32_kernel(const b
             init[1] = __builtin_bit_cast(floatx4, r1);
         }
         floatx4 X[2][2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) X[qb][kb] = init[qb];
         if constexpr (PROBS) {
-            staged_rows_times_resident<ST + Q_TILE>(row_addr, resident, init, X);   // Q K^T - lse / scale
+            staged_rows_times_resident<ST + Q_TILE>(row_addr, resident, X);         // Q K^T - lse / scale
             StagedTransposedProduct<ST + G_TILE> g_t;
             g_t.prefetch(tr_addr);
             __builtin_amdgcn_sched_barrier(0);
@@ -794,7 +946,7 @@ __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_x32_kernel(const b
             __builtin_amdgcn_s_barrier();
             g_t.run(tr_addr, Pb, acc);                                              // dV^T += dO^T P
         } else {
-            staged_rows_times_resident<ST + G_TILE>(row_addr, resident, init, X);   // dO V^T - delta
+            staged_rows_times_resident<ST + G_TILE>(row_addr, resident, X);         // dO V^T - delta
             StagedTransposedProduct<ST + Q_TILE> q_t;
             q_t.prefetch(tr_addr);
             __builtin_amdgcn_s_barrier();
@@ -1132,7 +1284,7 @@ hipError_t launch_backward(const void *q, const void *k, const void *v, const vo
     // 18.5, 18.5, 19.3 ms.
     const uint32_t chunk = p.n_w * (p.P / kCols);
     dim3 block(kNW * 64);
-    sta_bwd_dq_kernel<2><<<grid_for(chunk), block, 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_q), p, win, n_bh, chunk);
+    sta_bwd_dq_x32_kernel<<<grid_for(chunk), block, 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_q), p, win, n_bh, chunk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.P % 192 == 0) {
