@@ -9,7 +9,7 @@
 //   dQ_i  = scale * sum_j dS_ij K_j    dK_j = scale * sum_i dS_ij Q_i
 //
 // Three kernels, no atomics, results repeatable:
-//   sta_bwd_delta_kernel  delta_i for every query row (HBM-bound, reads O and dO once);
+//   sta_bwd_delta_kernel  -delta_i and -lse_i / scale for every query row (HBM-bound, reads O and dO once);
 //   sta_bwd_dq_kernel     one workgroup per query block, walks the key tiles of its window (as the forward
 //                         kernel does): 3 MFMA products per block (K Q^T, V dO^T, K^T dS^T);
 //   sta_bwd_dkv_kernel    one workgroup per key block, walks the QUERY tiles that keep its key tile (the
@@ -17,16 +17,13 @@
 //                         over pairs of waves.
 // S and dP are thus computed twice (7 products against the 5 of a single-pass scheme with atomics on dQ).
 //
-// Same MFMA formulation as the forward kernel: the block is held transposed so that one lane owns one column
-// (a query in the dQ kernel, a key in the dK/dV kernel), and the bf16-rounded P or dS goes from the
-// accumulators straight into the B operand of the next product, the contraction index being fed in
-// accumulator order.  Staged operands sit row-major in LDS (256 B per token), brought in by
-// global_load_lds.  An operand may be read both by rows (A rows = tokens, 16-byte reads) and transposed
-// (A rows = channels, ds_read_b64_tr_b16); one XOR swizzle of the 16-byte chunks keeps both conflict-free:
-// chunk c of row r sits at position c ^ swz(r), swz(r) = ((r & 3) << 2) | ((r >> 2) & 3).  Over 16 consecutive
-// rows swz takes 16 different values (row reads of one chunk column hit 16 different bank groups), and over the
-// 4 rows a transposing read touches its upper two bits differ (the four 64-byte channel groups go to four
-// different quarters of the row).
+// Same MFMA formulation as the forward kernel (v_mfma_f32_16x16x32_bf16, the shape that costs the least energy per
+// flop on this power-limited chip): the block is held so that one lane owns one column (a query in the dQ kernel,
+// a key in the dK/dV kernel), and the bf16-rounded P or dS goes from the accumulators straight into the B operand
+// of the next product, the contraction index being fed in accumulator order.  Staged operands are brought in by
+// global_load_lds; an operand may be read both by rows (A rows = tokens, 16-byte reads) and transposed (A rows =
+// channels, ds_read_b64_tr_b16), and one LDS layout serves both without bank conflicts (described where the two
+// products are defined).
 // These kernels: head dimension 128, tokens per tile a multiple of 128.  Other shapes (head dimension 64, tiles
 // that are multiples of 32 tokens) go through the simple kernels further down.
 #include <hip/hip_runtime.h>
@@ -41,91 +38,10 @@ namespace {
 constexpr int kD = 128;
 constexpr int kRowB = kD * 2;          // bytes per token row
 constexpr int kSub = 32;               // tokens per staged sub-block
-constexpr int kTileB = kSub * kRowB;   // 8 KB: one staged operand
 constexpr int kNW = 4;                 // waves per workgroup, 32 columns each
 constexpr int kCols = kNW * 32;        // queries (dQ kernel) or keys (dK/dV kernel) per workgroup
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-
-__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
-
-// Byte offset, inside a row-major [32][128] bf16 sub-block in global memory, of the 16-byte chunk that belongs
-// at LDS slot `slot` (0..15) of row `row`.
-__device__ __forceinline__ uint32_t src_chunk_offset(int row, int slot)
-{
-    return (uint32_t)(row * kRowB + ((slot ^ swz(row)) << 4));
-}
-
-// Issue the 8 transposing reads of one 16-token group.  The second read of each pair is 8 rows further down,
-// where swz differs in bit 1, so it has its own address.
-template <int BASE>
-__device__ __forceinline__ void tr_issue(shortx4 (&frag)[4][2], const uint32_t (&tr_addr)[2][4])
-{
-    static_for<0, 4>([&](auto dbi) {
-        constexpr int db = decltype(dbi)::value;
-        frag[db][0] = ds_read_tr16<BASE>(tr_addr[0][db]);
-        frag[db][1] = ds_read_tr16<BASE + 8 * kRowB>(tr_addr[1][db]);
-    });
-}
-
-// acc(32 x 32) = init + A B with A = a staged sub-block read by rows (A rows = its 32 tokens, k = channels) at byte
-// offset OFF of LDS, and B = eight resident fragments (k = channels).  Reads go out one group of four k-steps
-// ahead of the MFMAs that use them.
-template <int OFF>
-__device__ __forceinline__ floatx16 rows_times_resident(const uint32_t (&row_addr)[8], const bf16x8 (&resident)[8],
-                                                        const floatx16 &init)
-{
-    floatx16 acc = init;
-    bf16x8 frag[2][4];
-    k_issue<0, kRowB, OFF>(frag[0], row_addr);
-    k_issue<1, kRowB, OFF>(frag[1], row_addr);
-    k_wait<4>(frag[0]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) acc = mfma_32x32x16(frag[0][i], resident[i], acc);
-    __builtin_amdgcn_sched_barrier(0);
-    k_wait<0>(frag[1]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) acc = mfma_32x32x16(frag[1][i], resident[4 + i], acc);
-    __builtin_amdgcn_sched_barrier(0);
-    return acc;
-}
-
-// acc[db](32 channels x 32 columns) += A B with A = the staged sub-block at OFF read transposed (A rows =
-// channels, k = its 32 tokens in accumulator order) and B = the two packed halves of an accumulator.  The
-// reads of the first 16 tokens can be issued early (prefetch), before B exists, so that their latency hides
-// behind the arithmetic that produces B.
-template <int OFF>
-struct TransposedProduct {
-    shortx4 frag[2][4][2];
-    __device__ __forceinline__ void prefetch(const uint32_t (&tr_addr)[2][4]) { tr_issue<OFF>(frag[0], tr_addr); }
-    __device__ __forceinline__ void run(const uint32_t (&tr_addr)[2][4], const bf16x8 (&packed)[2], floatx16 (&acc)[4])
-    {
-        typedef short shortx8 __attribute__((ext_vector_type(8)));
-        tr_issue<OFF + 16 * kRowB>(frag[1], tr_addr);
-        pv_wait<8>(frag[0]);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            const shortx8 a = __builtin_shufflevector(frag[0][db][0], frag[0][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
-            acc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, a), packed[0], acc[db]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        pv_wait<0>(frag[1]);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-            const shortx8 a = __builtin_shufflevector(frag[1][db][0], frag[1][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
-            acc[db] = mfma_32x32x16(__builtin_bit_cast(bf16x8, a), packed[1], acc[db]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    }
-};
-
-__device__ __forceinline__ void pack16(const float (&x)[16], bf16x8 (&out)[2])
-{
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) out[j][e] = static_cast<__bf16>(x[8 * j + e]);
-}
 
 // Walks the sub-blocks of the tiles of a box; next_row is the first token row (tiled order, inside the head) of
 // the sub-block to request next.  Along each axis the box [lo, hi] holds e = hi-lo+1 consecutive tiles, hence
@@ -190,50 +106,6 @@ __device__ __forceinline__ bool work_item(uint32_t chunk, uint32_t blocks_per_he
     return true;
 }
 
-// Per-lane constants of the operand reads (relative to the start of a staged sub-block).
-//  Row reads: row lo, logical chunk 2*ks + hb.
-//  Transposing reads: within each block of 16 lanes, lane 4*j4 + s4 supplies 4 channels of token row
-//  4*hb + j4 (+8 for the second read of a pair); logical chunk 4*db + 2*blk + (s4 >> 1), 8-byte half s4 & 1.
-__device__ __forceinline__ void operand_addresses(uint32_t smem_addr, int lane, uint32_t (&row_addr)[8],
-                                                  uint32_t (&tr_addr)[2][4])
-{
-    const int lo = lane & 31, hb = lane >> 5;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) row_addr[ks] = smem_addr + (uint32_t)(lo * kRowB + (((2 * ks + hb) ^ swz(lo)) << 4));
-    const int j4 = (lane & 15) >> 2, s4 = lane & 3, blk = (lane >> 4) & 1;
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
-        const int row = 4 * hb + j4 + 8 * a;             // the +8 itself travels in the instruction's immediate
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-            tr_addr[a][db] = smem_addr + (uint32_t)((4 * hb + j4) * kRowB +
-                                                    (((4 * db + 2 * blk + (s4 >> 1)) ^ swz(row)) << 4) + 8 * (s4 & 1));
-    }
-}
-
-// Resident B-operand fragments of this wave's 32 columns (rows of x): column lo, channels 16*ks + 8*hb ..
-__device__ __forceinline__ void load_resident(const bf16_raw *rows, int lane, bf16x8 (&frag)[8])
-{
-    const int lo = lane & 31, hb = lane >> 5;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) frag[ks] = *reinterpret_cast<const bf16x8 *>(rows + (size_t)lo * kD + ks * 16 + hb * 8);
-}
-
-// Stores the transposed accumulator (channels x 32 columns) times `mul` as bf16 rows of `dst`.
-__device__ __forceinline__ void store_columns(bf16_raw *dst, int lane, const floatx16 (&acc)[4], float mul)
-{
-    const int lo = lane & 31, hb = lane >> 5;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            bf16x4 ov;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) ov[t] = static_cast<__bf16>(acc[db][4 * g + t] * mul);
-            *reinterpret_cast<bf16x4 *>(dst + (size_t)lo * kD + db * 32 + g * 8 + hb * 4) = ov;
-        }
-}
-
 // ---------------------------------------------------------------------------------------------------------
 // Row statistics in the form the two kernels below start their accumulators with: neg_delta_i = -(dO_i . O_i)
 // and neg_lse_i = -lse_i / scale, so that the matrix instructions deliver dP - delta and S - lse / scale and
@@ -265,294 +137,26 @@ __global__ __launch_bounds__(256) void sta_bwd_delta_kernel(const uint4 *__restr
     }
 }
 
-// ---------------------------------------------------------------------------------------------------------
-// dQ.  One workgroup per 128 queries.  LDS stage: K (read by rows and transposed) and V (read by rows).
-// ---------------------------------------------------------------------------------------------------------
-template <int STAGES>
-__global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw *__restrict__ q,
-                                                                 const bf16_raw *__restrict__ k,
-                                                                 const bf16_raw *__restrict__ v,
-                                                                 const bf16_raw *__restrict__ d_o,
-                                                                 const float *__restrict__ neg_lse,
-                                                                 const float *__restrict__ neg_delta,
-                                                                 bf16_raw *__restrict__ d_q, sta::FwdParams p,
-                                                                 sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
-{
-    constexpr int OPS = 2, STAGE_B = OPS * kTileB;
-    constexpr int K_TILE = 0, V_TILE = kTileB;
-    __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_B];
-    static_assert(STAGES * STAGE_B <= 65536, "operand reads carry the stage as a 16-bit immediate offset");
-
-    uint32_t qblock, bh_rank;
-    if (!work_item(chunk, p.N / kCols, n_bh, &qblock, &bh_rank)) return;
-    const uint32_t heads = p.heads;
-    const uint32_t h_local = bh_rank % heads, b = bh_rank / heads;
-    const size_t bh = (size_t)b * p.H + p.head_base + h_local;
-    const uint32_t q_tile = (qblock * kCols) / p.P;
-    const StaBox box = sta_key_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1], win.w[h_local][2],
-                                           q_tile);
-    const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lane = tid & 63, lo = lane & 31;
-
-    const size_t my_row = bh * p.N + (size_t)qblock * kCols + (size_t)wave * 32;
-    const char *kh = reinterpret_cast<const char *>(k + bh * p.N * kD);
-    const char *vh = reinterpret_cast<const char *>(v + bh * p.N * kD);
-
-    // DMA: each operand is 8 instructions of 1 KB (4 rows); wave w issues instructions 2w and 2w+1 of each.
-    uint32_t src_off[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) src_off[i] = src_chunk_offset(4 * (2 * wave + i) + (lane >> 4), lane & 15);
-    auto issue_loads = [&](int stage, uint32_t first_row) {
-        const size_t base = (size_t)first_row * kRowB;
-        char *dst = smem + stage * STAGE_B + (2 * wave) * 1024;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + base + src_off[i]),
-                                             STA_LDS_PTR(dst + K_TILE + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + base + src_off[i]),
-                                             STA_LDS_PTR(dst + V_TILE + i * 1024), 16, 0, 0);
-        }
-    };
-
-    uint32_t row_addr[8], tr_addr[2][4];
-    operand_addresses((uint32_t)(uintptr_t)smem, lane, row_addr, tr_addr);
-
-    bf16x8 Qr[8], Gr[8];
-    load_resident(q + my_row * kD, lane, Qr);
-    load_resident(d_o + my_row * kD, lane, Gr);
-    const float c = p.scale_log2e;
-    // a lane owns one query column: its 16 accumulator registers all start at that query's statistic
-    floatx16 s_init, dp_init;
-    {
-        const float a = neg_lse[my_row + lo], b = neg_delta[my_row + lo];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            s_init[r] = a;
-            dp_init[r] = b;
-        }
-    }
-
-    floatx16 dQ[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) dQ[db][r] = 0.f;
-
-    BoxWalk walk;
-    walk.start(box, p.n_h, p.n_w, p.P);
-    const int n_iter = box.count() * walk.sub_per_tile;
-    // Up to STAGES - 1 sub-blocks are in flight; each is 4 DMA instructions per wave, returned in order.
-    int issued = 0, dma_stage = 0;
-    auto issue_next = [&]() {
-        if (issued < n_iter) {
-            issue_loads(dma_stage, walk.next_row);
-            dma_stage = dma_stage == STAGES - 1 ? 0 : dma_stage + 1;
-            walk.advance();
-            ++issued;
-        }
-    };
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s) issue_next();
-
-    auto sub_block = [&](auto stage_c, int iter) {
-        constexpr int ST = decltype(stage_c)::value * STAGE_B;
-        if (STAGES == 2 || issued - 1 - iter == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        __syncthreads();
-        issue_next();
-        const floatx16 S = rows_times_resident<ST + K_TILE>(row_addr, Qr, s_init);     // K Q^T - lse / scale
-        const floatx16 dP = rows_times_resident<ST + V_TILE>(row_addr, Gr, dp_init);   // V dO^T - delta
-        TransposedProduct<ST + K_TILE> k_t;
-        k_t.prefetch(tr_addr);
-        float ds[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float prob = __builtin_amdgcn_exp2f(S[r] * c);
-            ds[r] = prob * dP[r];
-        }
-        bf16x8 dSb[2];
-        pack16(ds, dSb);
-        k_t.run(tr_addr, dSb, dQ);                                              // dQ^T += K^T dS^T
-    };
-    for (int iter = 0; iter < n_iter; iter += STAGES) {
-        static_for<0, STAGES>([&](auto st) {
-            if (iter + decltype(st)::value < n_iter) sub_block(st, iter + decltype(st)::value);
-        });
-    }
-    store_columns(d_q + my_row * kD, lane, dQ, c * kLn2);
-}
-
-// ---------------------------------------------------------------------------------------------------------
-// dK, dV.  One workgroup of 8 waves per 128 keys.  LDS stage: Q and dO (each read by rows and transposed).
-// The four 32-key column blocks of the workgroup are each served by a PAIR of waves (w and w + 4, which
-// share a SIMD): wave w holds K and accumulates dV (S = Q K^T, P, dV^T += dO^T P), wave w + 4 holds V and
-// accumulates dK (dP = dO V^T, dS = P o (dP - delta), dK^T += Q^T dS).  P, rounded to bf16 and packed as the
-// MFMA B operand, goes from the first to the second through 2 KB of LDS.  Four matrix products per block, no
-// duplicate work inside the kernel, and each wave keeps one accumulator set: 2 waves per SIMD fit.
-// ---------------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void lds_write_b128(uint32_t addr, bf16x8 v)
 {
     asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory");
 }
 
-__global__ __launch_bounds__(512, 1) void sta_bwd_dkv_kernel(const bf16_raw *__restrict__ q,
-                                                             const bf16_raw *__restrict__ k,
-                                                             const bf16_raw *__restrict__ v,
-                                                             const bf16_raw *__restrict__ d_o,
-                                                             const float *__restrict__ neg_lse,
-                                                             const float *__restrict__ neg_delta,
-                                                             bf16_raw *__restrict__ d_k,
-                                                             bf16_raw *__restrict__ d_v, sta::FwdParams p,
-                                                             sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
-{
-    constexpr int OPS = 2, STAGE_B = OPS * kTileB;
-    constexpr int Q_TILE = 0, G_TILE = kTileB;
-    constexpr int P_XCHG = 2 * STAGE_B;                 // 4 column blocks x 2 planes x 64 lanes x 16 B
-    constexpr int STATS = P_XCHG + 4 * 2048;            // per stage: lse then delta of the 32 staged query rows
-    constexpr int STAT_B = 2 * kSub * 4;
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B + 4 * 2048 + 2 * STAT_B];
-
-    uint32_t kblock, bh_rank;
-    if (!work_item(chunk, p.N / kCols, n_bh, &kblock, &bh_rank)) return;
-    const uint32_t heads = p.heads;
-    const uint32_t h_local = bh_rank % heads, b = bh_rank / heads;
-    const size_t bh = (size_t)b * p.H + p.head_base + h_local;
-    const uint32_t k_tile = (kblock * kCols) / p.P;
-    const StaBox box = sta_query_tile_box_of(p.n_t, p.n_h, p.n_w, win.w[h_local][0], win.w[h_local][1],
-                                             win.w[h_local][2], k_tile);
-    const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lane = tid & 63, hb = lane >> 5;
-    const bool probs_role = wave < 4;                   // S, P, dV; the other role: dP, dS, dK
-    const int col_block = wave & 3;
-
-    const size_t head_row = bh * p.N;
-    const size_t my_row = head_row + (size_t)kblock * kCols + (size_t)col_block * 32;
-    const char *qh = reinterpret_cast<const char *>(q + head_row * kD);
-    const char *gh = reinterpret_cast<const char *>(d_o + head_row * kD);
-
-    // DMA: each operand is 8 instructions of 1 KB (4 rows); wave w issues instruction w of each.
-    const int dma_row = 4 * wave + (lane >> 4);
-    const uint32_t src_off = src_chunk_offset(dma_row, lane & 15);
-    // Row statistics of the staged sub-block (-lse / scale for the first role, -delta for the second) travel with it: one
-    // 4-byte-per-lane DMA instruction of the last wave brings the 32 + 32 floats into LDS, and every wave reads the
-    // rows 8*g + 4*hb + t its accumulator registers belong to from there.  (Loading them from global memory into
-    // registers in every wave, 32 wide loads per sub-block and CU, cost 2 ms of the launch.)
-    const float *stat_src = (lane < kSub ? neg_lse : neg_delta) + head_row + (lane & (kSub - 1));
-    auto issue_loads = [&](int stage, uint32_t first_row) {
-        const size_t base = (size_t)first_row * kRowB;
-        char *dst = smem + stage * STAGE_B + wave * 1024;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + src_off),
-                                         STA_LDS_PTR(dst + Q_TILE), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + src_off),
-                                         STA_LDS_PTR(dst + G_TILE), 16, 0, 0);
-        if (wave == 7)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(stat_src + first_row),
-                                             STA_LDS_PTR(smem + STATS + stage * STAT_B), 4, 0, 0);
-    };
-
-    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
-    uint32_t row_addr[8], tr_addr[2][4];
-    operand_addresses(smem_addr, lane, row_addr, tr_addr);
-    const uint32_t xchg_addr = smem_addr + P_XCHG + col_block * 2048 + lane * 16;   // two planes of 1 KB, contiguous per wave
-
-    bf16x8 resident[8];                                  // K rows (first role) or V rows (second role)
-    load_resident((probs_role ? k : v) + my_row * kD, lane, resident);
-    const float c = p.scale_log2e;
-
-    floatx16 acc[4];                                     // dV^T (first role) or dK^T (second role)
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
-
-    BoxWalk walk;
-    walk.start(box, p.n_h, p.n_w, p.P);
-    const int n_iter = box.count() * walk.sub_per_tile;
-    int issued = 0;
-    auto issue_next = [&]() {
-        if (issued < n_iter) {
-            issue_loads(issued & 1, walk.next_row);
-            walk.advance();
-            ++issued;
-        }
-    };
-    issue_next();
-
-    auto sub_block = [&](auto stage_c) {
-        constexpr int ST = decltype(stage_c)::value * STAGE_B;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();       // the stage is complete; the other stage and the exchange buffer are free
-        issue_next();
-        floatx16 st;           // the accumulators of the first product start at the statistics of their rows
-        {
-            const char *stats = smem + STATS + decltype(stage_c)::value * STAT_B + (probs_role ? 0 : kSub * 4) + 16 * hb;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const floatx4 x = *reinterpret_cast<const floatx4 *>(stats + 32 * g);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) st[4 * g + t] = x[t];
-            }
-        }
-        floatx16 X;
-        if (probs_role) {
-            X = rows_times_resident<ST + Q_TILE>(row_addr, resident, st);       // Q K^T - lse / scale (queries x keys)
-            TransposedProduct<ST + G_TILE> g_t;
-            g_t.prefetch(tr_addr);
-            float prob[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) prob[r] = __builtin_amdgcn_exp2f(X[r] * c);
-            bf16x8 Pb[2];
-            pack16(prob, Pb);
-            lds_write_b128(xchg_addr, Pb[0]);
-            lds_write_b128(xchg_addr + 1024, Pb[1]);
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            g_t.run(tr_addr, Pb, acc);                                          // dV^T += dO^T P
-        } else {
-            X = rows_times_resident<ST + G_TILE>(row_addr, resident, st);       // dO V^T - delta
-            TransposedProduct<ST + Q_TILE> q_t;
-            q_t.prefetch(tr_addr);
-            __builtin_amdgcn_s_barrier();
-            bf16x8 Pb[2];
-            Pb[0] = ds_read_b128_at<0>(xchg_addr);
-            Pb[1] = ds_read_b128_at<1024>(xchg_addr);
-            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(Pb[0]), "+v"(Pb[1]));
-            float ds[16];
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) ds[8 * j + e] = static_cast<float>(Pb[j][e]) * X[8 * j + e];
-            bf16x8 dSb[2];
-            pack16(ds, dSb);
-            q_t.run(tr_addr, dSb, acc);                                         // dK^T += Q^T dS
-        }
-    };
-    for (int iter = 0; iter < n_iter; iter += 2) {
-        sub_block(std::integral_constant<int, 0>{});
-        if (iter + 1 < n_iter) sub_block(std::integral_constant<int, 1>{});
-    }
-    if (probs_role) store_columns(d_v + my_row * kD, lane, acc, 1.0f);
-    else store_columns(d_k + my_row * kD, lane, acc, c * kLn2);
-}
-
-
 // ---------------------------------------------------------------------------------------------------------
-// dK, dV on v_mfma_f32_16x16x32_bf16.  One workgroup of 2 * NPAIR waves per 32 * NPAIR keys; the same split of the
-// four products over pairs of waves as above, in the forward kernel's register layout: a lane holds key column
-// c16 = lane & 15 of a 16x16 result and the query rows 4*g4 .. 4*g4+3 (g4 = lane >> 4); a wave's 32 keys are two
-// key blocks, and every fragment read from LDS feeds both.  Per wave and 32-query sub-block: 32 matrix
-// instructions, 40 vector instructions, 26 LDS reads, in 168 registers, so that three waves per SIMD fit (six
-// pairs: 192 keys per workgroup, every staged Q / dO sub-block serves 1.5 times the columns it served above).
-// LDS layout of a staged operand: groups of 4 rows (1 KB, one DMA instruction), kStagedGroup = 1024 + 32 bytes
-// apart, chunk c of row j of a group at c ^ (j << 2).  It serves both ways of reading without bank conflicts:
+// Staged operands and the two kinds of product.  Register layout of v_mfma_f32_16x16x32_bf16: a lane holds column
+// c16 = lane & 15 of a 16x16 result and the rows 4*g4 .. 4*g4+3 (g4 = lane >> 4); of an operand it holds row/column
+// c16 and the k-chunk 8*g4 .. 8*g4+7.  A wave's 32 columns are two blocks of 16, and every fragment read from LDS
+// feeds both.
+// LDS layout of a staged operand (32 token rows of 256 bytes): groups of 4 rows (1 KB, one DMA instruction),
+// kStagedGroup = 1024 + 32 bytes apart, chunk c of row j of a group at c ^ (j << 2).  It serves both ways of reading
+// without bank conflicts:
 //  - by rows (16-byte reads, served for lanes 0-7 together with 24-31, i.e. rows 0..7 at chunk x with rows 8..15
 //    at chunk x ^ 1): the four rows of a group land in the four quarters of the 256 bytes, and consecutive groups
 //    are turned by 32 bytes, which together with the odd chunk of the second half covers all sixteen positions;
 //  - transposed (8-byte reads, served 32 lanes at a time: 8 consecutive rows, two neighbouring chunks each).
-// The stage, the operand, the query block of a row read and the odd channel blocks of a transposing read are
-// offsets inside the instructions: a wave keeps four row addresses (one per k-step) and four transposing ones.
+// The stage, the operand, the row block of a row read and the odd channel blocks of a transposing read are
+// offsets inside the instructions: a wave keeps four row addresses (one per k-step) and four transposing ones,
+// and no address is computed inside the loop.
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kStagedGroup = 1024 + 32;
 constexpr int kStagedTile = (kSub / 4) * kStagedGroup;      // one staged operand of 32 rows
@@ -638,13 +242,13 @@ struct StagedTransposedProduct {
 };
 
 // ---------------------------------------------------------------------------------------------------------
-// dQ on v_mfma_f32_16x16x32_bf16.  One workgroup of 4 waves per 128 queries, two workgroups per CU; a lane holds query
+// dQ.  One workgroup of 4 waves per 128 queries, two workgroups per CU (206 registers); a lane holds query
 // column c16 of its wave's two 16-query blocks.  LDS stage: K (read by rows and transposed) and V (read by rows), in
 // the layout described above.  Per wave and 32-key sub-block: S^T = K Q^T - lse / scale and dP^T = V dO^T - delta
 // (16 matrix instructions each, the statistics of the lane's query as the initial value), dS^T = 2^(c S^T) o dP^T,
 // dQ^T += K^T dS^T (16).
 // ---------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_x32_kernel(const bf16_raw *__restrict__ q,
+__global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw *__restrict__ q,
                                                                      const bf16_raw *__restrict__ k,
                                                                      const bf16_raw *__restrict__ v,
                                                                      const bf16_raw *__restrict__ d_o,
@@ -690,7 +294,11 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_x32_kernel(const bf16_
         }
     };
 
-    // per-lane constants of the operand reads (as in the dK/dV kernel, with key rows in the place of query rows)
+    // Per-lane constants of the operand reads, relative to the start of a staged operand.
+    //  Row reads (A = 16 keys x 32 channels): row c16 = row c16 & 3 of group c16 >> 2, logical chunk 4*ks + g4.
+    //  Transposing reads (A = 16 channels x 32 keys): within each block of 16 lanes, lane 4*j4 + s4 supplies
+    //  channels 4*s4 .. 4*s4+3 of the block's 16 of key row 4*g4 + j4 = row j4 of group g4; logical chunk
+    //  2*cb + (s4 >> 1), one address per value of cb >> 1.
     const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
     uint32_t row_addr[4], tr_addr[4];
     {
@@ -789,8 +397,18 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_x32_kernel(const bf16_
         }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// dK, dV.  One workgroup of 2 * NPAIR waves per 32 * NPAIR keys.  Each 32-key column block is served by a PAIR of
+// waves: the first holds K and accumulates dV (S = Q K^T, P, dV^T += dO^T P), the second holds V and accumulates dK
+// (dP = dO V^T, dS = P o (dP - delta), dK^T += Q^T dS).  P, rounded to bf16 and packed as the MFMA B operand, goes
+// from the first to the second through 2 KB of LDS.  Four matrix products per block, no duplicate work inside the
+// kernel, and each wave keeps one accumulator set: per wave and 32-query sub-block 32 matrix instructions, 40 vector
+// instructions and 26 LDS reads in 158 registers, so that three waves per SIMD fit (six pairs: 192 keys per
+// workgroup).  LDS stage: Q and dO (each read by rows and transposed) and the row statistics of the 32 queries.
+// A lane holds key column c16 of its wave's two 16-key blocks and the query rows 4*g4 .. 4*g4+3 of a result.
+// ---------------------------------------------------------------------------------------------------------
 template <int NPAIR>
-__global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_x32_kernel(const bf16_raw *__restrict__ q,
+__global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_kernel(const bf16_raw *__restrict__ q,
                                                                          const bf16_raw *__restrict__ k,
                                                                          const bf16_raw *__restrict__ v,
                                                                          const bf16_raw *__restrict__ d_o,
@@ -852,11 +470,7 @@ __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_x32_kernel(const b
                 STA_LDS_PTR(smem + STATS + stage * STAT_B), 4, 0, 0);
     };
 
-    // Per-lane constants of the operand reads, relative to the start of a staged operand.
-    //  Row reads (A = 16 queries x 32 channels): row c16 = row c16 & 3 of group c16 >> 2, logical chunk 4*ks + g4.
-    //  Transposing reads (A = 16 channels x 32 queries): within each block of 16 lanes, lane 4*j4 + s4 supplies
-    //  channels 4*s4 .. 4*s4+3 of the block's 16 of query row 4*g4 + j4 = row j4 of group g4; logical chunk
-    //  2*cb + (s4 >> 1), one address per value of cb >> 1.
+    // per-lane constants of the operand reads (as in the dQ kernel, with query rows in the place of key rows)
     const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
     uint32_t row_addr[4], tr_addr[4];
     {
@@ -995,6 +609,14 @@ __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_x32_kernel(const b
 // row-major LDS block without swizzle (the row reads take bank conflicts), one sub-block at a time.  The fast
 // kernels above take over where they apply.
 // ---------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void pack16(const float (&x)[16], bf16x8 (&out)[2])
+{
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[j][e] = static_cast<__bf16>(x[8 * j + e]);
+}
+
 template <int D>
 struct GenericOps {
     static constexpr int RowB = 2 * D;             // bytes per token row
@@ -1284,17 +906,17 @@ hipError_t launch_backward(const void *q, const void *k, const void *v, const vo
     // 18.5, 18.5, 19.3 ms.
     const uint32_t chunk = p.n_w * (p.P / kCols);
     dim3 block(kNW * 64);
-    sta_bwd_dq_x32_kernel<<<grid_for(chunk), block, 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_q), p, win, n_bh, chunk);
+    sta_bwd_dq_kernel<<<grid_for(chunk), block, 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_q), p, win, n_bh, chunk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.P % 192 == 0) {
         // 192 keys per workgroup: the chunk is again one row of tiles along w
         const uint32_t total6 = (p.N / 192) * n_bh, chunk6 = p.n_w * (p.P / 192);
         const dim3 grid6(8 * chunk6 * ((((total6 + chunk6 - 1) / chunk6) + 7) / 8));
-        sta_bwd_dkv_x32_kernel<6><<<grid6, dim3(768), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_k),
+        sta_bwd_dkv_kernel<6><<<grid6, dim3(768), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_k),
                                                                   static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk6);
     } else {
-        sta_bwd_dkv_x32_kernel<4><<<grid_for(chunk), dim3(512), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta,
+        sta_bwd_dkv_kernel<4><<<grid_for(chunk), dim3(512), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta,
                                                                             static_cast<bf16_raw *>(d_k),
                                                                             static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk);
     }
