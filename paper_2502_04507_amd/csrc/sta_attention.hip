@@ -948,29 +948,34 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
     const int start_t = box.t.lo + (e_t - box.t.lo % e_t) % e_t;
     const int start_h = box.h.lo + (e_h - box.h.lo % e_h) % e_h;
     const int start_w = box.w.lo + (e_w - box.w.lo % e_w) % e_w;
-    int it_t = start_t, it_h = start_h, it_w = start_w, it_s = 0;
-    int left_h = e_h, left_w = e_w;         // tiles still to visit in the current h-cycle / w-cycle
+    int it_t, it_h, it_w, it_s;
+    int left_h, left_w;                     // tiles still to visit in the current h-cycle / w-cycle
     auto row_start = [&]() -> size_t {      // byte offset of key tile (it_t, it_h, it_w) inside the head
         const size_t kt = ((size_t)it_t * p.n_h + it_h) * p.n_w + it_w;
         return kt * p.P * ROWB;
     };
-    // a part starts iter_lo sub-blocks into the walk: whole tiles first, then sub-blocks inside the tile
-    for (int skip = iter_lo / sub_per_tile; skip > 0; --skip) {
-        if (++it_w > box.w.hi) it_w = box.w.lo;
-        if (--left_w == 0) {
-            left_w = e_w;
-            it_w = start_w;
-            if (++it_h > box.h.hi) it_h = box.h.lo;
-            if (--left_h == 0) {
-                left_h = e_h;
-                it_h = start_h;
-                if (++it_t > box.t.hi) it_t = box.t.lo;
+    size_t next_base;
+    auto start_walk = [&]() __attribute__((always_inline)) {
+        it_t = start_t; it_h = start_h; it_w = start_w;
+        left_h = e_h; left_w = e_w;
+        // a part starts iter_lo sub-blocks into the walk: whole tiles first, then sub-blocks inside the tile
+        for (int skip = iter_lo / sub_per_tile; skip > 0; --skip) {
+            if (++it_w > box.w.hi) it_w = box.w.lo;
+            if (--left_w == 0) {
+                left_w = e_w;
+                it_w = start_w;
+                if (++it_h > box.h.hi) it_h = box.h.lo;
+                if (--left_h == 0) {
+                    left_h = e_h;
+                    it_h = start_h;
+                    if (++it_t > box.t.hi) it_t = box.t.lo;
+                }
             }
         }
-    }
-    it_s = iter_lo % sub_per_tile;
-    size_t next_base = row_start() + (size_t)it_s * KB * ROWB;
-    auto advance = [&]() {
+        it_s = iter_lo % sub_per_tile;
+        next_base = row_start() + (size_t)it_s * KB * ROWB;
+    };
+    auto advance = [&]() __attribute__((always_inline)) {
         next_base += (size_t)KB * ROWB;
         if (++it_s == sub_per_tile) {
             it_s = 0;
@@ -1001,16 +1006,21 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
 
     // ---- pipeline: up to STAGES-1 sub-blocks are in flight.  (it_t, it_h, it_w, it_s) always names the next
     // sub-block to request; `issued` counts the requests made so far.
-    int issued = 0;
-    auto issue_next = [&]() {
+    int issued;
+    auto issue_next = [&]() __attribute__((always_inline)) {
         if (issued < n_iter) {
             if (wave < LOADERS) issue_loads(issued % STAGES, next_base);
             advance();
             ++issued;
         }
     };
+    auto start_pipeline = [&]() __attribute__((always_inline)) {
+        start_walk();
+        issued = 0;
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s) issue_next();
+        for (int s = 0; s < STAGES - 1; ++s) issue_next();
+    };
+    start_pipeline();
 
     // One sub-block.  The loop is not unrolled over the two stages (unrolled, the register allocator gives the
     // accumulators different registers in the two copies and copies all 64 once per pair of sub-blocks); the stage
@@ -1018,7 +1028,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
     // (lds_off: where the stage begins; it enters the operand base addresses at run time)
     // units of the accumulated scores: base-2 exponents if Q was scaled, raw dot products otherwise
     const float c = PRESCALE ? 1.f : p.scale_log2e;
-    auto sub_block_at = [&](uint32_t lds_off, float grow_above) {
+    auto sub_block_at = [&](auto track_c, uint32_t lds_off, float grow_above) __attribute__((always_inline)) {
+        constexpr bool TRACK = decltype(track_c)::value;   // follow the growth of the scores in this sub-block
         const uint32_t kb_ = k_base + lds_off;
         uint32_t vb_[4];
 #pragma unroll
@@ -1074,36 +1085,38 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
         // lanes; only when some lane reports growth is the row maximum formed over the four lanes of a query, so
         // that all of them move to the same offset.  grow_above is that bound in the units of the scores, or -infinity
         // in an item's first sub-block.
-        float mq[2];
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            mq[qb] = max3(S[0][qb][0], S[0][qb][1], S[0][qb][2]);
-            mq[qb] = max3(mq[qb], S[0][qb][3], S[1][qb][0]);
-            mq[qb] = max3(mq[qb], S[1][qb][1], S[1][qb][2]);
-        }
-        const float mx = max3(max3(mq[0], S[1][0][3], mq[1]), S[1][1][3], S[1][1][3]);
-        if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > grow_above) != 0, 0)) {
-#pragma unroll
+        if constexpr (TRACK) {
+            float mq[2];
+    #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
-                const float row_max = quad_lane_max(fmaxf(mq[qb], S[1][qb][3]));
-                const float shift = row_max > grow_above ? row_max : 0.f;     // the same in the four lanes of a query
-                // shift is negative only in a first sub-block, where the accumulators are still zero
-                const float alpha = __builtin_amdgcn_exp2f(fminf(-shift, 0.f) * c);
-                m_run[qb] += shift;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) Sinit[qb][r] = -m_run[qb];
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) S[kb][qb][r] -= shift;
-                l_run[qb] *= alpha;
-                // in place: written as plain multiplications the register allocator gives the scaled accumulators
-                // new registers and then copies all 64 on the path that does NOT rescale
-                // (the compiler does not see into the assembly: the wait state that a vector instruction needs before
-                // it reads the result of a transcendental one is given by hand)
-                const float alpha_settled = settled_after_transcendental(alpha);
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb) scale_in_place(Oacc[cb][qb], alpha_settled);
+                mq[qb] = max3(S[0][qb][0], S[0][qb][1], S[0][qb][2]);
+                mq[qb] = max3(mq[qb], S[0][qb][3], S[1][qb][0]);
+                mq[qb] = max3(mq[qb], S[1][qb][1], S[1][qb][2]);
+            }
+            const float mx = max3(max3(mq[0], S[1][0][3], mq[1]), S[1][1][3], S[1][1][3]);
+            if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > grow_above) != 0, 0)) {
+    #pragma unroll
+                for (int qb = 0; qb < 2; ++qb) {
+                    const float row_max = quad_lane_max(fmaxf(mq[qb], S[1][qb][3]));
+                    const float shift = row_max > grow_above ? row_max : 0.f;     // the same in the four lanes of a query
+                    // shift is negative only in a first sub-block, where the accumulators are still zero
+                    const float alpha = __builtin_amdgcn_exp2f(fminf(-shift, 0.f) * c);
+                    m_run[qb] += shift;
+    #pragma unroll
+                    for (int r = 0; r < 4; ++r) Sinit[qb][r] = -m_run[qb];
+    #pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+    #pragma unroll
+                        for (int r = 0; r < 4; ++r) S[kb][qb][r] -= shift;
+                    l_run[qb] *= alpha;
+                    // in place: written as plain multiplications the register allocator gives the scaled accumulators
+                    // new registers and then copies all 64 on the path that does NOT rescale
+                    // (the compiler does not see into the assembly: the wait state that a vector instruction needs before
+                    // it reads the result of a transcendental one is given by hand)
+                    const float alpha_settled = settled_after_transcendental(alpha);
+    #pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) scale_in_place(Oacc[cb][qb], alpha_settled);
+                }
             }
         }
         // first group of V-operand reads (channel blocks 0..3) goes out once the offsets are settled (no
@@ -1168,20 +1181,52 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
     };
 
     const uint32_t bound_bits = __builtin_amdgcn_readfirstlane(__float_as_uint(8.0f / c));
-#pragma unroll 1
-    for (int iter = 0; iter < n_iter; ++iter) {
+    auto next_sub_block = [&]() __attribute__((always_inline)) {
         // this wave's DMA for this sub-block must have landed (the only requests outstanding)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();   // ... and everyone's; the stage read in the previous iteration is free again
-        issue_next();      // refills stage (iter - 1) % STAGES
-        // growth threshold: 2^8 in the units of the scores, -infinity for the first keys of an item
-        sub_block_at((uint32_t)((iter & 1) * STAGE_BYTES), __uint_as_float(iter == 0 ? 0xff800000u : bound_bits));
+        issue_next();      // refills the other stage
+    };
+    // The first sub-block of an item sets the offsets (row maxima of its 32 keys).  After that the common case needs
+    // no offset to move: probabilities, row sums and accumulators are fp32 or bf16 numbers with 8 exponent bits,
+    // whose relative precision does not depend on their size, so an offset that turns out too low costs nothing
+    // until the sums near the end of that range.  The remaining sub-blocks therefore run WITHOUT following the
+    // maximum (ten vector instructions and a branch less per sub-block), and the row sums are looked at once at the
+    // end: if one of them is beyond 2^64 or not a number, the workgroup does the whole item again with the careful
+    // loop, which re-bases whenever a score exceeds the offset by more than 2^8 in the exponent.
+    next_sub_block();
+    sub_block_at(std::true_type{}, 0u, __uint_as_float(0xff800000u));
+#pragma unroll 1
+    for (int iter = 1; iter < n_iter; ++iter) {
+        next_sub_block();
+        sub_block_at(std::false_type{}, (uint32_t)((iter & 1) * STAGE_BYTES), 0.f);
     }
-
-    // ---- finalize -------------------------------------------------------------------
     float l_tot[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) l_tot[qb] = quad_lane_sum(l_run[qb]);
+    constexpr float kRedoAbove = 18446744073709551616.f;      // 2^64
+    // (the comparison is false for a NaN; the barrier inside also ends every wave's reads of the stages)
+    if (__builtin_expect(__syncthreads_or(!(l_tot[0] < kRedoAbove && l_tot[1] < kRedoAbove)), 0)) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            m_run[qb] = 0.f;
+            l_run[qb] = 0.f;
+            Sinit[qb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) Oacc[cb][qb] = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+        start_pipeline();
+#pragma unroll 1
+        for (int iter = 0; iter < n_iter; ++iter) {
+            next_sub_block();
+            // growth threshold: 2^8 in the units of the scores, -infinity for the first keys of an item
+            sub_block_at(std::true_type{}, (uint32_t)((iter & 1) * STAGE_BYTES), __uint_as_float(iter == 0 ? 0xff800000u : bound_bits));
+        }
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) l_tot[qb] = quad_lane_sum(l_run[qb]);
+    }
+
+    // ---- finalize -------------------------------------------------------------------
     if (is_part) {
         // unnormalised accumulator, offset and row sum of this part; the combine kernel does the rest
         float *ws = p.split_ws + (size_t)(blockIdx.x - p.split_first) * split_part_floats<D>(QB);

@@ -192,6 +192,27 @@ def test_attention_running_max_keeps_growing(tile, grid):
         gu.assert_parity(out[0, h], ref, "growmax h%d" % h)
 
 
+@pytest.mark.parametrize("tile,grid", [((6, 8, 8), (6, 16, 24)), ((2, 8, 8), (4, 16, 16))])
+def test_attention_scores_outgrow_the_first_offset(tile, grid):
+    """The first keys of every window give scores near zero, later ones scores of many tens: an exponent offset
+    that is set by the first sub-block and then left alone lets the row sums leave the range of fp32 (2^100 and
+    beyond).  The kernel has to notice and do such items again with offsets that follow the scores.  Both
+    kernel shapes (384- and 128-token tiles)."""
+    w = syn.custom("outgrow", 1, 2, 128, grid, tile, [(1, 3, 3), (3, 3, 3)], "bf16", seed=84)
+    q, k, v = syn.make_qkv(w)
+    order = torch.from_numpy(orc.tile_order(w.grid, w.tile))
+    ramp_tiled = torch.linspace(0.02, 14.0, w.N)                    # grows along the TILED sequence
+    ramp = torch.empty(w.N)
+    ramp[order] = ramp_tiled
+    k = (k.float() * ramp[None, None, :, None]).to(torch.bfloat16)
+    q = (q.float() * 2.0).to(torch.bfloat16)
+    out = gu.gpu_chain(w, q, k, v).float().numpy()
+    assert np.isfinite(out).all()
+    for h in range(2):
+        ref = gu.oracle_rows(w, q, k, v, 0, h, None)
+        gu.assert_parity(out[0, h], ref, "outgrow h%d" % h)
+
+
 def test_attention_large_scores_stay_finite():
     """Scores of a few hundred before scaling: exponent offsets must keep everything finite."""
     w = syn.custom("bigscores", 1, 1, 128, (6, 8, 16), (6, 8, 8), [(1, 1, 3)], "bf16", seed=80)
