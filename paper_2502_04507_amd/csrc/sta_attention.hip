@@ -545,29 +545,34 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_
     const int start_t = box.t.lo + (e_t - box.t.lo % e_t) % e_t;
     const int start_h = box.h.lo + (e_h - box.h.lo % e_h) % e_h;
     const int start_w = box.w.lo + (e_w - box.w.lo % e_w) % e_w;
-    int it_t = start_t, it_h = start_h, it_w = start_w, it_s = 0;
-    int left_h = e_h, left_w = e_w;         // tiles still to visit in the current h-cycle / w-cycle
+    int it_t, it_h, it_w, it_s;
+    int left_h, left_w;                     // tiles still to visit in the current h-cycle / w-cycle
     auto row_start = [&]() -> size_t {      // byte offset of key tile (it_t, it_h, it_w) inside the head
         const size_t kt = ((size_t)it_t * p.n_h + it_h) * p.n_w + it_w;
         return kt * p.P * ROWB;
     };
-    // a part starts iter_lo sub-blocks into the walk: whole tiles first, then sub-blocks inside the tile
-    for (int skip = iter_lo / sub_per_tile; skip > 0; --skip) {
-        if (++it_w > box.w.hi) it_w = box.w.lo;
-        if (--left_w == 0) {
-            left_w = e_w;
-            it_w = start_w;
-            if (++it_h > box.h.hi) it_h = box.h.lo;
-            if (--left_h == 0) {
-                left_h = e_h;
-                it_h = start_h;
-                if (++it_t > box.t.hi) it_t = box.t.lo;
+    size_t next_base;
+    auto start_walk = [&]() __attribute__((always_inline)) {
+        it_t = start_t; it_h = start_h; it_w = start_w;
+        left_h = e_h; left_w = e_w;
+        // a part starts iter_lo sub-blocks into the walk: whole tiles first, then sub-blocks inside the tile
+        for (int skip = iter_lo / sub_per_tile; skip > 0; --skip) {
+            if (++it_w > box.w.hi) it_w = box.w.lo;
+            if (--left_w == 0) {
+                left_w = e_w;
+                it_w = start_w;
+                if (++it_h > box.h.hi) it_h = box.h.lo;
+                if (--left_h == 0) {
+                    left_h = e_h;
+                    it_h = start_h;
+                    if (++it_t > box.t.hi) it_t = box.t.lo;
+                }
             }
         }
-    }
-    it_s = iter_lo % sub_per_tile;
-    size_t next_base = row_start() + (size_t)it_s * KB * ROWB;
-    auto advance = [&]() {
+        it_s = iter_lo % sub_per_tile;
+        next_base = row_start() + (size_t)it_s * KB * ROWB;
+    };
+    auto advance = [&]() __attribute__((always_inline)) {
         next_base += (size_t)KB * ROWB;
         if (++it_s == sub_per_tile) {
             it_s = 0;
@@ -599,20 +604,27 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_
 
     // ---- pipeline: up to STAGES-1 sub-blocks are in flight.  (it_t, it_h, it_w, it_s) always names the next
     // sub-block to request; `issued` counts the requests made so far.
-    int issued = 0;
-    auto issue_next = [&]() {
+    int issued;
+    auto issue_next = [&]() __attribute__((always_inline)) {
         if (issued < n_iter) {
             if (wave < LOADERS) issue_loads(issued % STAGES, next_base);
             advance();
             ++issued;
         }
     };
+    auto start_pipeline = [&]() __attribute__((always_inline)) {
+        start_walk();
+        issued = 0;
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s) issue_next();
+        for (int s = 0; s < STAGES - 1; ++s) issue_next();
+    };
+    start_pipeline();
 
     // One sub-block.  The LDS stage is a compile-time constant here (the loop below is unrolled over the
     // stages), so every operand read carries its stage as an immediate offset and needs no address arithmetic.
-    auto sub_block = [&](auto stage_c, int iter) {
+    // TRACK: follow the growth of the scores in this sub-block (see the loops below).
+    auto sub_block = [&](auto track_c, auto stage_c, int iter) __attribute__((always_inline)) {
+        constexpr bool TRACK = decltype(track_c)::value;
         constexpr int stage = decltype(stage_c)::value;
         constexpr int KOFF = stage * STAGE_BYTES;
         constexpr int VOFF = KOFF + TILE_BYTES;
@@ -653,26 +665,28 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_
         pv_issue<VOFF, DB, ROWB>(va[0], v_addr);
 
         // ---- online softmax: one query column per lane ------------------------------
-        float mx = max3(S[0][0], S[0][1], S[0][2]);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-            for (int r = (mb == 0 ? 3 : 1); r + 1 < 16; r += 2) mx = max3(mx, S[mb][r], S[mb][r + 1]);
-            mx = max3(mx, S[mb][15], mb == 0 ? S[mb][15] : S[mb][0]);
-        }
-        mx = half_swap_max(mx);
-        // Lazy rescale: the exponent offset only moves when the max grew by more than 2^8 in the
-        // exponent, so probabilities stay below 256 and the accumulators are rarely touched.
-        const bool grow = (mx - m_run) * c > 8.0f;
-        if (__builtin_amdgcn_ballot_w64(grow)) {
-            const float m_new = grow ? mx : m_run;
-            const float alpha = exp2f((m_run - m_new) * c);
-            m_run = m_new;
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) Oacc[db][r] *= alpha;
+        if constexpr (TRACK) {
+            float mx = max3(S[0][0], S[0][1], S[0][2]);
+    #pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+    #pragma unroll
+                for (int r = (mb == 0 ? 3 : 1); r + 1 < 16; r += 2) mx = max3(mx, S[mb][r], S[mb][r + 1]);
+                mx = max3(mx, S[mb][15], mb == 0 ? S[mb][15] : S[mb][0]);
+            }
+            mx = half_swap_max(mx);
+            // Lazy rescale: the exponent offset only moves when the max grew by more than 2^8 in the
+            // exponent, so probabilities stay below 256 and the accumulators are rarely touched.
+            const bool grow = (mx - m_run) * c > 8.0f;
+            if (__builtin_amdgcn_ballot_w64(grow)) {
+                const float m_new = grow ? mx : m_run;
+                const float alpha = exp2f((m_run - m_new) * c);
+                m_run = m_new;
+                l_run *= alpha;
+    #pragma unroll
+                for (int db = 0; db < DB; ++db)
+    #pragma unroll
+                    for (int r = 0; r < 16; ++r) Oacc[db][r] *= alpha;
+            }
         }
         const float mneg = -m_run * c;
         bf16x8 Pb[MB][2];
@@ -718,14 +732,39 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_
         });
     };
 
-    for (int iter = 0; iter < n_iter; iter += STAGES) {
+    // The first sub-block of an item sets the exponent offset (the row maxima of its keys).  The rest runs without
+    // following the maximum: probabilities, row sums and accumulators have 8 exponent bits, so an offset that
+    // turns out too low costs no precision until the sums near the end of that range.  The row sums are looked at
+    // once at the end; if one is beyond 2^64 or not a number, the workgroup does the whole item again with the
+    // careful loop, which moves the offset whenever a score exceeds it by more than 2^8 in the exponent.
+    sub_block(std::true_type{}, std::integral_constant<int, 0>{}, 0);
+    for (int iter = 1; iter < n_iter; iter += STAGES) {
         static_for<0, STAGES>([&](auto st) {
-            if (iter + decltype(st)::value < n_iter) sub_block(st, iter + decltype(st)::value);
+            constexpr int stage = (1 + decltype(st)::value) % STAGES;       // sub-block i sits in stage i % STAGES
+            if (iter + decltype(st)::value < n_iter)
+                sub_block(std::false_type{}, std::integral_constant<int, stage>{}, iter + decltype(st)::value);
         });
+    }
+    float l_tot = half_swap_sum(l_run);
+    constexpr float kRedoAbove = 18446744073709551616.f;      // 2^64
+    // (the comparison is false for a NaN; the barrier inside also ends every wave's reads of the stages)
+    if (__builtin_expect(__syncthreads_or(!(l_tot < kRedoAbove)), 0)) {
+        m_run = -INFINITY;
+        l_run = 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Oacc[db][r] = 0.f;
+        start_pipeline();
+        for (int iter = 0; iter < n_iter; iter += STAGES) {
+            static_for<0, STAGES>([&](auto st) {
+                if (iter + decltype(st)::value < n_iter) sub_block(std::true_type{}, st, iter + decltype(st)::value);
+            });
+        }
+        l_tot = half_swap_sum(l_run);
     }
 
     // ---- finalize -------------------------------------------------------------------
-    const float l_tot = half_swap_sum(l_run);
     if (is_part) {
         // unnormalised accumulator, offset and row sum of this part; the combine kernel does the rest
         float *ws = p.split_ws + (size_t)(blockIdx.x - p.split_first) * split_part_floats<D>(QB);

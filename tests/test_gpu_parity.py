@@ -192,13 +192,16 @@ def test_attention_running_max_keeps_growing(tile, grid):
         gu.assert_parity(out[0, h], ref, "growmax h%d" % h)
 
 
-@pytest.mark.parametrize("tile,grid", [((6, 8, 8), (6, 16, 24)), ((2, 8, 8), (4, 16, 16))])
-def test_attention_scores_outgrow_the_first_offset(tile, grid):
+@pytest.mark.parametrize("tile,grid,D,windows", [
+    ((6, 8, 8), (6, 16, 24), 128, [(1, 3, 3), (3, 3, 3)]), ((2, 8, 8), (4, 16, 16), 128, [(1, 3, 3), (3, 3, 3)]),
+    ((6, 8, 8), (6, 16, 24), 64, [(1, 3, 3), (3, 3, 3)]), ((2, 8, 8), (4, 16, 16), 64, [(1, 3, 3), (3, 3, 3)]),
+    ((1, 8, 8), (1, 32, 32), 64, [(1, 3, 3), (1, 3, 5)])])
+def test_attention_scores_outgrow_the_first_offset(tile, grid, D, windows):
     """The first keys of every window give scores near zero, later ones scores of many tens: an exponent offset
     that is set by the first sub-block and then left alone lets the row sums leave the range of fp32 (2^100 and
-    beyond).  The kernel has to notice and do such items again with offsets that follow the scores.  Both
-    kernel shapes (384- and 128-token tiles)."""
-    w = syn.custom("outgrow", 1, 2, 128, grid, tile, [(1, 3, 3), (3, 3, 3)], "bf16", seed=84)
+    beyond).  The kernel has to notice and do such items again with offsets that follow the scores.  Every
+    shape of the DMA-staged kernels (384-, 128- and 64-token tiles, head dimension 128 and 64)."""
+    w = syn.custom("outgrow", 1, 2, D, grid, tile, windows, "bf16", seed=84)
     q, k, v = syn.make_qkv(w)
     order = torch.from_numpy(orc.tile_order(w.grid, w.tile))
     ramp_tiled = torch.linspace(0.02, 14.0, w.N)                    # grows along the TILED sequence
