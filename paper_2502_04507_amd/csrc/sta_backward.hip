@@ -24,8 +24,8 @@
 // global_load_lds; an operand may be read both by rows (A rows = tokens, 16-byte reads) and transposed (A rows =
 // channels, ds_read_b64_tr_b16), and one LDS layout serves both without bank conflicts (described where the two
 // products are defined).
-// These kernels: head dimension 128, tokens per tile a multiple of 128.  Other shapes (head dimension 64, tiles
-// that are multiples of 32 tokens) go through the simple kernels further down.
+// These kernels: head dimension 64 or 128, tokens per tile a multiple of 128.  Other shapes (tiles that are other
+// multiples of 32 tokens) go through the simple kernels further down.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -35,8 +35,6 @@
 
 namespace {
 
-constexpr int kD = 128;
-constexpr int kRowB = kD * 2;          // bytes per token row
 constexpr int kSub = 32;               // tokens per staged sub-block
 constexpr int kNW = 4;                 // waves per workgroup, 32 columns each
 constexpr int kCols = kNW * 32;        // queries (dQ kernel) or keys (dK/dV kernel) per workgroup
@@ -110,18 +108,20 @@ __device__ __forceinline__ bool work_item(uint32_t chunk, uint32_t blocks_per_he
 // Row statistics in the form the two kernels below start their accumulators with: neg_delta_i = -(dO_i . O_i)
 // and neg_lse_i = -lse_i / scale, so that the matrix instructions deliver dP - delta and S - lse / scale and
 // neither a subtraction nor a fused multiply-add per element is left (P = 2^(scale * log2(e) * (S - lse / scale))).
-// One 16-lane group per row (each lane 16 bytes of the 256-byte row).
+// One group of D / 8 lanes per row (each lane 16 bytes of it).
 // ---------------------------------------------------------------------------------------------------------
+template <int D>
 __global__ __launch_bounds__(256) void sta_bwd_delta_kernel(const uint4 *__restrict__ o, const uint4 *__restrict__ d_o,
                                                             const float *__restrict__ lse, float inv_scale,
                                                             float *__restrict__ neg_delta, float *__restrict__ neg_lse,
                                                             size_t rows)
 {
-    const size_t row = (size_t)blockIdx.x * 16 + (threadIdx.x >> 4);
-    const int part = threadIdx.x & 15;
+    constexpr int LPR = D / 8;                          // lanes per row
+    const size_t row = (size_t)blockIdx.x * (256 / LPR) + (threadIdx.x / LPR);
+    const int part = threadIdx.x % LPR;
     float acc = 0.f;
     if (row < rows) {
-        const uint4 a = o[row * 16 + part], b = d_o[row * 16 + part];
+        const uint4 a = o[row * LPR + part], b = d_o[row * LPR + part];
         const uint32_t as[4] = {a.x, a.y, a.z, a.w}, bs[4] = {b.x, b.y, b.z, b.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void sta_bwd_delta_kernel(const uint4 *__restr
         }
     }
 #pragma unroll
-    for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 16);
+    for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, LPR);
     if (row < rows && part == 0) {
         neg_delta[row] = -acc;
         neg_lse[row] = -lse[row] * inv_scale;
@@ -147,85 +147,154 @@ __device__ __forceinline__ void lds_write_b128(uint32_t addr, bf16x8 v)
 // c16 = lane & 15 of a 16x16 result and the rows 4*g4 .. 4*g4+3 (g4 = lane >> 4); of an operand it holds row/column
 // c16 and the k-chunk 8*g4 .. 8*g4+7.  A wave's 32 columns are two blocks of 16, and every fragment read from LDS
 // feeds both.
-// LDS layout of a staged operand (32 token rows of 256 bytes): groups of 4 rows (1 KB, one DMA instruction),
-// kStagedGroup = 1024 + 32 bytes apart, chunk c of row j of a group at c ^ (j << 2).  It serves both ways of reading
-// without bank conflicts:
+// LDS layout of a staged operand (32 token rows).  A DMA instruction fills 1 KB, and a lane's place in it is fixed
+// (16 * lane), so any swizzle is applied on the global side: the lane fetches the chunk that belongs at its place.
+//  Head dimension 128 (rows of 256 bytes = all 64 banks): groups of 4 rows, 1024 + 32 bytes apart, chunk c of row j
+//  of a group at c ^ (j << 2).
 //  - by rows (16-byte reads, served for lanes 0-7 together with 24-31, i.e. rows 0..7 at chunk x with rows 8..15
 //    at chunk x ^ 1): the four rows of a group land in the four quarters of the 256 bytes, and consecutive groups
 //    are turned by 32 bytes, which together with the odd chunk of the second half covers all sixteen positions;
 //  - transposed (8-byte reads, served 32 lanes at a time: 8 consecutive rows, two neighbouring chunks each).
-// The stage, the operand, the row block of a row read and the odd channel blocks of a transposing read are
-// offsets inside the instructions: a wave keeps four row addresses (one per k-step) and four transposing ones,
-// and no address is computed inside the loop.
+//  The stage, the operand, the row block of a row read and the odd channel blocks of a transposing read are
+//  offsets inside the instructions: a wave keeps four row addresses (one per k-step) and four transposing ones.
+//  Head dimension 64 (rows of 128 bytes, two rows span the banks): rows 128 bytes apart without padding, chunk c of
+//  row r at c ^ (((r >> 1) & 3) << 1).
+//  - by rows: even rows sit in the lower 128 bytes of a bank line and odd rows in the upper; rows 0, 2, 4, 6 at chunk
+//    x take the four even positions of their half, rows 8, 10, 12, 14 at chunk x ^ 1 the four odd ones;
+//  - transposed: rows 0, 2, 4, 6 take four different 32-byte pairs of their half, rows 1, 3, 5, 7 the same of theirs.
+//  A wave keeps two row addresses (one per k-step) and four transposing ones (one per channel block).
+// In both layouts no address is computed inside the loop.
 // ---------------------------------------------------------------------------------------------------------
-constexpr int kStagedGroup = 1024 + 32;
-constexpr int kStagedTile = (kSub / 4) * kStagedGroup;      // one staged operand of 32 rows
+template <int D>
+struct Staged {
+    static_assert(D == 64 || D == 128, "head dimension");
+    static constexpr int RowB = 2 * D;                          // bytes per token row
+    static constexpr int KS = D / 32;                           // k-steps of a product over the channels
+    static constexpr int CB = D / 16;                           // 16-channel blocks of an accumulator
+    static constexpr int GroupRows = 1024 / RowB;               // rows per DMA instruction: 4 or 8
+    static constexpr int Groups = kSub / GroupRows;             // DMA instructions per operand: 8 or 4
+    static constexpr int Group = D == 128 ? 1024 + 32 : 1024;   // bytes from one group to the next
+    static constexpr int Tile = Groups * Group;                 // one staged operand
+    static constexpr int Rows16 = (16 / GroupRows) * Group;     // from row r to row r + 16
 
-// X[rb][cb] (16 staged rows x 16 resident columns) += A B: A = the staged operand at byte offset OFF read by rows
+    // where the 16-byte chunk c of row r (0..31) of a staged operand sits, in bytes from its start
+    static __device__ __forceinline__ uint32_t place(int r, int c)
+    {
+        if constexpr (D == 128) return (uint32_t)((r >> 2) * Group + (r & 3) * RowB + ((c ^ ((r & 3) << 2)) << 4));
+        else return (uint32_t)(r * RowB + ((c ^ (((r >> 1) & 3) << 1)) << 4));
+    }
+    // byte offset, inside a DMA group of the source (GroupRows rows, contiguous), of what the lane fetches
+    static __device__ __forceinline__ uint32_t dma_lane_offset(int lane)
+    {
+        constexpr int LPR = RowB / 16;                          // lanes (chunks) per row
+        const int r = lane / LPR, pos = lane % LPR;             // row inside the group, place inside the row
+        if constexpr (D == 128) return (uint32_t)(r * RowB + ((pos ^ (r << 2)) << 4));
+        else return (uint32_t)(r * RowB + ((pos ^ (((r >> 1) & 3) << 1)) << 4));   // groups start at multiples of 8 rows
+    }
+    // Per-lane addresses of the operand reads, relative to the start of a staged operand at LDS address `base`.
+    //  Row reads (A = 16 tokens x 32 channels): token row c16 (+16 for the second row block), chunk 4*ks + g4.
+    //  Transposing reads (A = 16 channels x 32 tokens): within each block of 16 lanes, lane 4*j4 + s4 supplies
+    //  channels 4*s4 .. 4*s4+3 of the block's 16 of token row 4*g4 + j4 (+16 for the second read); chunk
+    //  2*cb + (s4 >> 1).  With 256-byte rows the XOR reaches cb >> 1 only (cb & 1 is 32 bytes in the instruction),
+    //  with 128-byte rows it reaches all of cb: four addresses either way.
+    static __device__ __forceinline__ void addresses(uint32_t base, int lane, uint32_t (&row_addr)[KS], uint32_t (&tr_addr)[4])
+    {
+        const int c16 = lane & 15, g4 = lane >> 4, j4 = c16 >> 2, s4 = lane & 3;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) row_addr[ks] = base + place(c16, 4 * ks + g4);
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+            tr_addr[m] = base + place(4 * g4 + j4, (D == 128 ? 4 * m : 2 * m) + (s4 >> 1)) + 8 * (s4 & 1);
+    }
+    static constexpr int tr_index(int cb) { return D == 128 ? cb >> 1 : cb; }
+    static constexpr int tr_offset(int cb) { return D == 128 ? (cb & 1) * 32 : 0; }
+};
+
+// X[rb][col] (16 staged rows x 16 resident columns) += A B: A = the staged operand at byte offset OFF read by rows
 // (k = channels), B = resident fragments of the wave's 32 columns; the caller has set X to the value the sums start
 // from.  Four reads in flight; a fragment feeds both column blocks, taken 0, 1, 1, 0, .. so that one operand changes
 // from one matrix instruction to the next.
-template <int OFF>
-__device__ __forceinline__ void staged_rows_times_resident(const uint32_t (&row_addr)[4], const bf16x8 (&resident)[2][4],
-                                                           floatx4 (&X)[2][2])
+template <int D, int OFF>
+__device__ __forceinline__ void staged_rows_times_resident(const uint32_t (&row_addr)[D / 32],
+                                                           const bf16x8 (&resident)[2][D / 32], floatx4 (&X)[2][2])
 {
-    constexpr int ROWS16 = OFF + 4 * kStagedGroup;                 // rows 16..31
-    bf16x8 a0 = ds_read_b128_at<OFF>(row_addr[0]), a1 = ds_read_b128_at<OFF>(row_addr[1]);
-    bf16x8 a2 = ds_read_b128_at<OFF>(row_addr[2]), a3 = ds_read_b128_at<OFF>(row_addr[3]);
-    lds_wait2<2>(a0, a1);
+    constexpr int ROWS16 = OFF + Staged<D>::Rows16;             // rows 16..31
+    if constexpr (D == 128) {
+        bf16x8 a0 = ds_read_b128_at<OFF>(row_addr[0]), a1 = ds_read_b128_at<OFF>(row_addr[1]);
+        bf16x8 a2 = ds_read_b128_at<OFF>(row_addr[2]), a3 = ds_read_b128_at<OFF>(row_addr[3]);
+        lds_wait2<2>(a0, a1);
 #pragma unroll
-    for (int col = 0; col < 2; ++col) X[0][col] = mfma_16x16x32(a0, resident[col][0], X[0][col]);
+        for (int col = 0; col < 2; ++col) X[0][col] = mfma_16x16x32(a0, resident[col][0], X[0][col]);
 #pragma unroll
-    for (int col = 1; col >= 0; --col) X[0][col] = mfma_16x16x32(a1, resident[col][1], X[0][col]);
-    __builtin_amdgcn_sched_barrier(0);
-    bf16x8 b0 = ds_read_b128_at<ROWS16>(row_addr[0]), b1 = ds_read_b128_at<ROWS16>(row_addr[1]);
-    lds_wait2<2>(a2, a3);
+        for (int col = 1; col >= 0; --col) X[0][col] = mfma_16x16x32(a1, resident[col][1], X[0][col]);
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 b0 = ds_read_b128_at<ROWS16>(row_addr[0]), b1 = ds_read_b128_at<ROWS16>(row_addr[1]);
+        lds_wait2<2>(a2, a3);
 #pragma unroll
-    for (int col = 0; col < 2; ++col) X[0][col] = mfma_16x16x32(a2, resident[col][2], X[0][col]);
+        for (int col = 0; col < 2; ++col) X[0][col] = mfma_16x16x32(a2, resident[col][2], X[0][col]);
 #pragma unroll
-    for (int col = 1; col >= 0; --col) X[0][col] = mfma_16x16x32(a3, resident[col][3], X[0][col]);
-    __builtin_amdgcn_sched_barrier(0);
-    bf16x8 b2 = ds_read_b128_at<ROWS16>(row_addr[2]), b3 = ds_read_b128_at<ROWS16>(row_addr[3]);
-    lds_wait2<2>(b0, b1);
+        for (int col = 1; col >= 0; --col) X[0][col] = mfma_16x16x32(a3, resident[col][3], X[0][col]);
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 b2 = ds_read_b128_at<ROWS16>(row_addr[2]), b3 = ds_read_b128_at<ROWS16>(row_addr[3]);
+        lds_wait2<2>(b0, b1);
 #pragma unroll
-    for (int col = 0; col < 2; ++col) X[1][col] = mfma_16x16x32(b0, resident[col][0], X[1][col]);
+        for (int col = 0; col < 2; ++col) X[1][col] = mfma_16x16x32(b0, resident[col][0], X[1][col]);
 #pragma unroll
-    for (int col = 1; col >= 0; --col) X[1][col] = mfma_16x16x32(b1, resident[col][1], X[1][col]);
-    __builtin_amdgcn_sched_barrier(0);
-    lds_wait2<0>(b2, b3);
+        for (int col = 1; col >= 0; --col) X[1][col] = mfma_16x16x32(b1, resident[col][1], X[1][col]);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_wait2<0>(b2, b3);
 #pragma unroll
-    for (int col = 0; col < 2; ++col) X[1][col] = mfma_16x16x32(b2, resident[col][2], X[1][col]);
+        for (int col = 0; col < 2; ++col) X[1][col] = mfma_16x16x32(b2, resident[col][2], X[1][col]);
 #pragma unroll
-    for (int col = 1; col >= 0; --col) X[1][col] = mfma_16x16x32(b3, resident[col][3], X[1][col]);
-    __builtin_amdgcn_sched_barrier(0);
+        for (int col = 1; col >= 0; --col) X[1][col] = mfma_16x16x32(b3, resident[col][3], X[1][col]);
+        __builtin_amdgcn_sched_barrier(0);
+    } else {
+        bf16x8 a0 = ds_read_b128_at<OFF>(row_addr[0]), a1 = ds_read_b128_at<OFF>(row_addr[1]);
+        bf16x8 b0 = ds_read_b128_at<ROWS16>(row_addr[0]), b1 = ds_read_b128_at<ROWS16>(row_addr[1]);
+        lds_wait2<2>(a0, a1);
+#pragma unroll
+        for (int col = 0; col < 2; ++col) X[0][col] = mfma_16x16x32(a0, resident[col][0], X[0][col]);
+#pragma unroll
+        for (int col = 1; col >= 0; --col) X[0][col] = mfma_16x16x32(a1, resident[col][1], X[0][col]);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_wait2<0>(b0, b1);
+#pragma unroll
+        for (int col = 0; col < 2; ++col) X[1][col] = mfma_16x16x32(b0, resident[col][0], X[1][col]);
+#pragma unroll
+        for (int col = 1; col >= 0; --col) X[1][col] = mfma_16x16x32(b1, resident[col][1], X[1][col]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 }
 
 // acc[cb][col] (16 channels x 16 resident columns) += A B: A = the staged operand at OFF read transposed (A rows =
 // channels, k = its 32 rows: index 8*g4 + i is row 4*g4 + i of the first 16 for i < 4, of the second 16 otherwise),
 // B = packed[col].  The reads of channel blocks 0..3 can go out before B exists.
-template <int OFF>
+template <int D, int OFF>
 struct StagedTransposedProduct {
-    shortx4 frag[2][4][2];
+    static constexpr int CB = D / 16;                   // channel blocks: read four at a time
+    static constexpr int NG = CB / 4;
+    shortx4 frag[NG][4][2];
     template <int G>
     __device__ __forceinline__ void issue(const uint32_t (&tr_addr)[4])
     {
         static_for<0, 4>([&](auto i) {
             constexpr int cb = 4 * G + decltype(i)::value;
-            frag[G][cb & 3][0] = ds_read_tr16<OFF + (cb & 1) * 32>(tr_addr[cb >> 1]);
-            frag[G][cb & 3][1] = ds_read_tr16<OFF + (cb & 1) * 32 + 4 * kStagedGroup>(tr_addr[cb >> 1]);
+            constexpr int at = OFF + Staged<D>::tr_offset(cb);
+            frag[G][cb & 3][0] = ds_read_tr16<at>(tr_addr[Staged<D>::tr_index(cb)]);
+            frag[G][cb & 3][1] = ds_read_tr16<at + Staged<D>::Rows16>(tr_addr[Staged<D>::tr_index(cb)]);
         });
     }
     __device__ __forceinline__ void prefetch(const uint32_t (&tr_addr)[4]) { issue<0>(tr_addr); }
-    __device__ __forceinline__ void run(const uint32_t (&tr_addr)[4], const bf16x8 (&packed)[2], floatx4 (&acc)[8][2])
+    __device__ __forceinline__ void run(const uint32_t (&tr_addr)[4], const bf16x8 (&packed)[2], floatx4 (&acc)[CB][2])
     {
         typedef short shortx8 __attribute__((ext_vector_type(8)));
-        static_for<0, 2>([&](auto gi) {
+        static_for<0, NG>([&](auto gi) {
             constexpr int g = decltype(gi)::value;
-            if constexpr (g == 0) {
-                issue<1>(tr_addr);
-                pv_wait<8>(frag[0]);
+            if constexpr (g + 1 < NG) {
+                issue<g + 1>(tr_addr);
+                pv_wait<8>(frag[g]);
             } else {
-                pv_wait<0>(frag[1]);
+                pv_wait<0>(frag[g]);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -242,23 +311,27 @@ struct StagedTransposedProduct {
 };
 
 // ---------------------------------------------------------------------------------------------------------
-// dQ.  One workgroup of 4 waves per 128 queries, two workgroups per CU (206 registers); a lane holds query
-// column c16 of its wave's two 16-query blocks.  LDS stage: K (read by rows and transposed) and V (read by rows), in
-// the layout described above.  Per wave and 32-key sub-block: S^T = K Q^T - lse / scale and dP^T = V dO^T - delta
-// (16 matrix instructions each, the statistics of the lane's query as the initial value), dS^T = 2^(c S^T) o dP^T,
-// dQ^T += K^T dS^T (16).
+// dQ.  One workgroup of 4 waves per 128 queries (two workgroups per CU at head dimension 128, 206 registers); a lane
+// holds query column c16 of its wave's two 16-query blocks.  LDS stage: K (read by rows and transposed) and V (read by
+// rows), in the layout described above.  Per wave and 32-key sub-block: S^T = K Q^T - lse / scale and
+// dP^T = V dO^T - delta (the statistics of the lane's query as the initial value), dS^T = 2^(c S^T) o dP^T,
+// dQ^T += K^T dS^T; 16 matrix instructions each at head dimension 128, 8 at 64.
 // ---------------------------------------------------------------------------------------------------------
+template <int D>
 __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw *__restrict__ q,
-                                                                     const bf16_raw *__restrict__ k,
-                                                                     const bf16_raw *__restrict__ v,
-                                                                     const bf16_raw *__restrict__ d_o,
-                                                                     const float *__restrict__ neg_lse,
-                                                                     const float *__restrict__ neg_delta,
-                                                                     bf16_raw *__restrict__ d_q, sta::FwdParams p,
-                                                                     sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
+                                                                 const bf16_raw *__restrict__ k,
+                                                                 const bf16_raw *__restrict__ v,
+                                                                 const bf16_raw *__restrict__ d_o,
+                                                                 const float *__restrict__ neg_lse,
+                                                                 const float *__restrict__ neg_delta,
+                                                                 bf16_raw *__restrict__ d_q, sta::FwdParams p,
+                                                                 sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
 {
-    constexpr int STAGE_B = 2 * kStagedTile;
-    constexpr int K_TILE = 0, V_TILE = kStagedTile;
+    using L = Staged<D>;
+    constexpr int KS = L::KS, CB = L::CB;
+    constexpr int STAGE_B = 2 * L::Tile;
+    constexpr int K_TILE = 0, V_TILE = L::Tile;
+    constexpr int LOADS = L::Groups / kNW;              // DMA instructions per operand and wave: 2 or 1
     __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_B];
 
     uint32_t qblock, bh_rank;
@@ -274,19 +347,19 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
     const int lane = tid & 63, c16 = lane & 15, g4 = lane >> 4;
 
     const size_t my_row = bh * p.N + (size_t)qblock * kCols + (size_t)wave * 32;
-    const char *kh = reinterpret_cast<const char *>(k + bh * p.N * kD);
-    const char *vh = reinterpret_cast<const char *>(v + bh * p.N * kD);
+    const char *kh = reinterpret_cast<const char *>(k + bh * p.N * D);
+    const char *vh = reinterpret_cast<const char *>(v + bh * p.N * D);
 
-    // DMA: each operand is 8 instructions of 1 KB (a group of 4 rows); wave w issues instructions 2w and 2w+1 of each.
-    const uint32_t src_lane_off = (uint32_t)(g4 * kRowB + ((c16 ^ (g4 << 2)) << 4));
+    // DMA: each operand is L::Groups instructions of 1 KB; wave w issues the groups LOADS * w .. of each.
+    const uint32_t src_lane_off = L::dma_lane_offset(lane);
     auto issue_loads = [&](int stage, uint32_t first_row) {
         uint32_t off = src_lane_off;
         asm volatile("" : "+v"(off));                   // keep the lane offset 32-bit next to a scalar base
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int group = 2 * wave + i;
-            const size_t base = (size_t)(first_row + 4 * group) * kRowB;
-            char *dst = smem + stage * STAGE_B + group * kStagedGroup;
+        for (int i = 0; i < LOADS; ++i) {
+            const int group = LOADS * wave + i;
+            const size_t base = (size_t)(first_row + L::GroupRows * group) * L::RowB;
+            char *dst = smem + stage * STAGE_B + group * L::Group;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kh + base + off),
                                              STA_LDS_PTR(dst + K_TILE), 16, 0, 0);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vh + base + off),
@@ -294,30 +367,16 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
         }
     };
 
-    // Per-lane constants of the operand reads, relative to the start of a staged operand.
-    //  Row reads (A = 16 keys x 32 channels): row c16 = row c16 & 3 of group c16 >> 2, logical chunk 4*ks + g4.
-    //  Transposing reads (A = 16 channels x 32 keys): within each block of 16 lanes, lane 4*j4 + s4 supplies
-    //  channels 4*s4 .. 4*s4+3 of the block's 16 of key row 4*g4 + j4 = row j4 of group g4; logical chunk
-    //  2*cb + (s4 >> 1), one address per value of cb >> 1.
-    const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
-    uint32_t row_addr[4], tr_addr[4];
-    {
-        const int j = c16 & 3, j4 = c16 >> 2, s4 = lane & 3;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            row_addr[ks] = smem_addr + (uint32_t)((c16 >> 2) * kStagedGroup + j * kRowB + ((((ks ^ j) << 2) | g4) << 4));
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-            tr_addr[m] = smem_addr + (uint32_t)(g4 * kStagedGroup + j4 * kRowB + ((((m ^ j4) << 2) | (s4 >> 1)) << 4) + 8 * (s4 & 1));
-    }
+    uint32_t row_addr[KS], tr_addr[4];
+    L::addresses((uint32_t)(uintptr_t)smem, lane, row_addr, tr_addr);
 
     // resident B fragments: query 16*qb + c16, channels 32*ks + 8*g4 ..
-    bf16x8 Qr[2][4], Gr[2][4];
+    bf16x8 Qr[2][KS], Gr[2][KS];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const size_t at = (my_row + 16 * qb + c16) * kD + ks * 32 + g4 * 8;
+        for (int ks = 0; ks < KS; ++ks) {
+            const size_t at = (my_row + 16 * qb + c16) * D + ks * 32 + g4 * 8;
             Qr[qb][ks] = *reinterpret_cast<const bf16x8 *>(q + at);
             Gr[qb][ks] = *reinterpret_cast<const bf16x8 *>(d_o + at);
         }
@@ -331,9 +390,9 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
         dp_init[qb] = floatx4{d, d, d, d};
     }
 
-    floatx4 dQ[8][2];                                   // [channel block][query block]
+    floatx4 dQ[CB][2];                                  // [channel block][query block]
 #pragma unroll
-    for (int cb = 0; cb < 8; ++cb)
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) dQ[cb][qb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
@@ -363,9 +422,9 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
                 S[kb][qb] = s_init[qb];
                 dP[kb][qb] = dp_init[qb];
             }
-        staged_rows_times_resident<ST + K_TILE>(row_addr, Qr, S);       // K Q^T - lse / scale
-        staged_rows_times_resident<ST + V_TILE>(row_addr, Gr, dP);      // V dO^T - delta
-        StagedTransposedProduct<ST + K_TILE> k_t;
+        staged_rows_times_resident<D, ST + K_TILE>(row_addr, Qr, S);    // K Q^T - lse / scale
+        staged_rows_times_resident<D, ST + V_TILE>(row_addr, Gr, dP);   // V dO^T - delta
+        StagedTransposedProduct<D, ST + K_TILE> k_t;
         k_t.prefetch(tr_addr);
         __builtin_amdgcn_sched_barrier(0);
         // dS^T, rounded to bf16 and packed as the B operand of the last product: k index 8*g4 + i is key 4*g4 + i
@@ -389,11 +448,11 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb) {
+        for (int cb = 0; cb < CB; ++cb) {
             bf16x4 ov;
 #pragma unroll
             for (int t = 0; t < 4; ++t) ov[t] = static_cast<__bf16>(dQ[cb][qb][t] * mul);
-            *reinterpret_cast<bf16x4 *>(d_q + (my_row + 16 * qb + c16) * kD + 16 * cb + 4 * g4) = ov;
+            *reinterpret_cast<bf16x4 *>(d_q + (my_row + 16 * qb + c16) * D + 16 * cb + 4 * g4) = ov;
         }
 }
 
@@ -402,30 +461,33 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
 // waves: the first holds K and accumulates dV (S = Q K^T, P, dV^T += dO^T P), the second holds V and accumulates dK
 // (dP = dO V^T, dS = P o (dP - delta), dK^T += Q^T dS).  P, rounded to bf16 and packed as the MFMA B operand, goes
 // from the first to the second through 2 KB of LDS.  Four matrix products per block, no duplicate work inside the
-// kernel, and each wave keeps one accumulator set: per wave and 32-query sub-block 32 matrix instructions, 40 vector
-// instructions and 26 LDS reads in 158 registers, so that three waves per SIMD fit (six pairs: 192 keys per
-// workgroup).  LDS stage: Q and dO (each read by rows and transposed) and the row statistics of the 32 queries.
+// kernel, and each wave keeps one accumulator set: at head dimension 128, per wave and 32-query sub-block 32 matrix
+// instructions, 40 vector instructions and 26 LDS reads in 158 registers, so that three waves per SIMD fit (six pairs:
+// 192 keys per workgroup).  LDS stage: Q and dO (each read by rows and transposed) and the row statistics of the 32 queries.
 // A lane holds key column c16 of its wave's two 16-key blocks and the query rows 4*g4 .. 4*g4+3 of a result.
 // ---------------------------------------------------------------------------------------------------------
-template <int NPAIR>
+template <int D, int NPAIR>
 __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_kernel(const bf16_raw *__restrict__ q,
-                                                                         const bf16_raw *__restrict__ k,
-                                                                         const bf16_raw *__restrict__ v,
-                                                                         const bf16_raw *__restrict__ d_o,
-                                                                         const float *__restrict__ neg_lse,
-                                                                         const float *__restrict__ neg_delta,
-                                                                         bf16_raw *__restrict__ d_k,
-                                                                         bf16_raw *__restrict__ d_v, sta::FwdParams p,
-                                                                         sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
+                                                                     const bf16_raw *__restrict__ k,
+                                                                     const bf16_raw *__restrict__ v,
+                                                                     const bf16_raw *__restrict__ d_o,
+                                                                     const float *__restrict__ neg_lse,
+                                                                     const float *__restrict__ neg_delta,
+                                                                     bf16_raw *__restrict__ d_k,
+                                                                     bf16_raw *__restrict__ d_v, sta::FwdParams p,
+                                                                     sta::WindowTable win, uint32_t n_bh, uint32_t chunk)
 {
+    using L = Staged<D>;
+    constexpr int KS = L::KS, CB = L::CB;
     constexpr int COLS = NPAIR * 32;                    // keys per workgroup
-    constexpr int STAGE_B = 2 * kStagedTile;
-    constexpr int Q_TILE = 0, G_TILE = kStagedTile;
+    constexpr int STAGE_B = 2 * L::Tile;
+    constexpr int Q_TILE = 0, G_TILE = L::Tile;
     constexpr int P_XCHG = 2 * STAGE_B;                 // per pair: 2 key blocks x 64 lanes x 16 B
     constexpr int STATS = P_XCHG + NPAIR * 2048;        // per stage: -lse / scale then -delta of the 32 staged query rows
     constexpr int STAT_B = 2 * kSub * 4;
-    constexpr int DMA_WAVES = kSub / 4;                 // one DMA instruction per operand and loading wave
+    constexpr int DMA_WAVES = 8;                        // waves that bring the operands in
     constexpr int STAT_WAVE = 2 * NPAIR > DMA_WAVES ? DMA_WAVES : DMA_WAVES - 1;   // a wave of its own where there is one
+    static_assert(2 * NPAIR >= DMA_WAVES, "eight loading waves");
     __shared__ __attribute__((aligned(1024))) char smem[STATS + 2 * STAT_B];
 
     uint32_t kblock, bh_rank;
@@ -444,25 +506,29 @@ __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_kernel(const bf16_
 
     const size_t head_row = bh * p.N;
     const size_t my_row = head_row + (size_t)kblock * COLS + (size_t)pair * 32;
-    const char *qh = reinterpret_cast<const char *>(q + head_row * kD);
-    const char *gh = reinterpret_cast<const char *>(d_o + head_row * kD);
+    const char *qh = reinterpret_cast<const char *>(q + head_row * D);
+    const char *gh = reinterpret_cast<const char *>(d_o + head_row * D);
 
-    // DMA: each operand is 8 instructions of 1 KB (a group of 4 rows); wave w < 8 issues instruction w of each.  The
-    // lane's slot in LDS is fixed (16 * lane), so it fetches the chunk that belongs there.  Wave 8 brings the row
-    // statistics of the sub-block (32 + 32 floats) with one 4-byte-per-lane instruction (wave 7 where there are eight).
-    const uint32_t src_lane_off = (uint32_t)(g4 * kRowB + ((c16 ^ (g4 << 2)) << 4));
+    // DMA: each operand is L::Groups instructions of 1 KB.  Head dimension 128 (8 per operand): wave w < 8 issues
+    // instruction w of each operand; head dimension 64 (4 per operand): waves 0..3 bring Q, waves 4..7 dO.  Wave 8
+    // brings the row statistics of the sub-block (32 + 32 floats) with one 4-byte-per-lane instruction (wave 7 where
+    // there are eight).
+    const uint32_t src_lane_off = L::dma_lane_offset(lane);
     const uint32_t stat_lane_off = (uint32_t)((lane & (kSub - 1)) * 4);
     const char *stat_base = reinterpret_cast<const char *>((lane < kSub ? neg_lse : neg_delta) + head_row);
     auto issue_loads = [&](int stage, uint32_t first_row) {
         uint32_t off = src_lane_off, soff = stat_lane_off;
         asm volatile("" : "+v"(off), "+v"(soff));       // keep the lane offsets 32-bit next to a scalar base
         if (wave < DMA_WAVES) {
-            const size_t base = (size_t)(first_row + 4 * wave) * kRowB;
-            char *dst = smem + stage * STAGE_B + wave * kStagedGroup;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off),
-                                             STA_LDS_PTR(dst + Q_TILE), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off),
-                                             STA_LDS_PTR(dst + G_TILE), 16, 0, 0);
+            const int group = D == 128 ? wave : (wave & 3);
+            const size_t base = (size_t)(first_row + L::GroupRows * group) * L::RowB;
+            char *dst = smem + stage * STAGE_B + group * L::Group;
+            if (D == 128 || wave < 4)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(qh + base + off),
+                                                 STA_LDS_PTR(dst + Q_TILE), 16, 0, 0);
+            if (D == 128 || wave >= 4)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gh + base + off),
+                                                 STA_LDS_PTR(dst + G_TILE), 16, 0, 0);
         }
         if (wave == STAT_WAVE)
             __builtin_amdgcn_global_load_lds(
@@ -470,36 +536,27 @@ __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_kernel(const bf16_
                 STA_LDS_PTR(smem + STATS + stage * STAT_B), 4, 0, 0);
     };
 
-    // per-lane constants of the operand reads (as in the dQ kernel, with query rows in the place of key rows)
     const uint32_t smem_addr = (uint32_t)(uintptr_t)smem;
-    uint32_t row_addr[4], tr_addr[4];
-    {
-        const int j = c16 & 3, j4 = c16 >> 2, s4 = lane & 3;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            row_addr[ks] = smem_addr + (uint32_t)((c16 >> 2) * kStagedGroup + j * kRowB + ((((ks ^ j) << 2) | g4) << 4));
-#pragma unroll
-        for (int m = 0; m < 4; ++m)
-            tr_addr[m] = smem_addr + (uint32_t)(g4 * kStagedGroup + j4 * kRowB + ((((m ^ j4) << 2) | (s4 >> 1)) << 4) + 8 * (s4 & 1));
-    }
+    uint32_t row_addr[KS], tr_addr[4];
+    L::addresses(smem_addr, lane, row_addr, tr_addr);
     const uint32_t xchg_addr = smem_addr + P_XCHG + pair * 2048 + lane * 16;   // two planes of 1 KB per pair
     const uint32_t stat_addr = smem_addr + STATS + (probs_role ? 0 : kSub * 4) + 16 * g4;
 
     // resident B fragments: K rows (first role) or V rows (second role) of key 16*kb + c16, channels 32*ks + 8*g4 ..
-    bf16x8 resident[2][4];
+    bf16x8 resident[2][KS];
     {
-        const bf16_raw *rows = (probs_role ? k : v) + my_row * kD;
+        const bf16_raw *rows = (probs_role ? k : v) + my_row * D;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                resident[kb][ks] = *reinterpret_cast<const bf16x8 *>(rows + (size_t)(16 * kb + c16) * kD + ks * 32 + g4 * 8);
+            for (int ks = 0; ks < KS; ++ks)
+                resident[kb][ks] = *reinterpret_cast<const bf16x8 *>(rows + (size_t)(16 * kb + c16) * D + ks * 32 + g4 * 8);
     }
     const float c = p.scale_log2e;
 
-    floatx4 acc[8][2];                                  // dV^T (first role) or dK^T (second role): [channel block][key block]
+    floatx4 acc[CB][2];                                 // dV^T (first role) or dK^T (second role): [channel block][key block]
 #pragma unroll
-    for (int cb = 0; cb < 8; ++cb)
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) acc[cb][kb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
@@ -542,8 +599,8 @@ __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_kernel(const bf16_
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) X[qb][kb] = init[qb];
         if constexpr (PROBS) {
-            staged_rows_times_resident<ST + Q_TILE>(row_addr, resident, X);         // Q K^T - lse / scale
-            StagedTransposedProduct<ST + G_TILE> g_t;
+            staged_rows_times_resident<D, ST + Q_TILE>(row_addr, resident, X);      // Q K^T - lse / scale
+            StagedTransposedProduct<D, ST + G_TILE> g_t;
             g_t.prefetch(tr_addr);
             __builtin_amdgcn_sched_barrier(0);
             bf16x8 Pb[2];
@@ -560,8 +617,8 @@ __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_kernel(const bf16_
             __builtin_amdgcn_s_barrier();
             g_t.run(tr_addr, Pb, acc);                                              // dV^T += dO^T P
         } else {
-            staged_rows_times_resident<ST + G_TILE>(row_addr, resident, X);         // dO V^T - delta
-            StagedTransposedProduct<ST + Q_TILE> q_t;
+            staged_rows_times_resident<D, ST + G_TILE>(row_addr, resident, X);      // dO V^T - delta
+            StagedTransposedProduct<D, ST + Q_TILE> q_t;
             q_t.prefetch(tr_addr);
             __builtin_amdgcn_s_barrier();
             bf16x8 Pb[2];
@@ -588,16 +645,16 @@ __global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_kernel(const bf16_
     if (probs_role) all_sub_blocks(std::true_type{});
     else all_sub_blocks(std::false_type{});
     // acc[cb][kb][i] = channel 16*cb + 4*g4 + i of key 16*kb + c16
-    bf16_raw *dst = (probs_role ? d_v : d_k) + my_row * kD;
+    bf16_raw *dst = (probs_role ? d_v : d_k) + my_row * D;
     const float mul = probs_role ? 1.0f : c * kLn2;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int cb = 0; cb < 8; ++cb) {
+        for (int cb = 0; cb < CB; ++cb) {
             bf16x4 ov;
 #pragma unroll
             for (int t = 0; t < 4; ++t) ov[t] = static_cast<__bf16>(acc[cb][kb][t] * mul);
-            *reinterpret_cast<bf16x4 *>(dst + (size_t)(16 * kb + c16) * kD + 16 * cb + 4 * g4) = ov;
+            *reinterpret_cast<bf16x4 *>(dst + (size_t)(16 * kb + c16) * D + 16 * cb + 4 * g4) = ov;
         }
 }
 
@@ -877,24 +934,20 @@ namespace sta {
 
 bool backward_supported(int P, int D) { return (D == 64 || D == 128) && P > 0 && P % kSub == 0; }
 
-hipError_t launch_backward(const void *q, const void *k, const void *v, const void *o, const void *d_o, const float *lse,
-                           float *delta, bool compute_delta, void *d_q, void *d_k, void *d_v, int B, int D,
-                           const FwdParams &p, const WindowTable &win, hipStream_t stream)
+// The three tuned kernels for head dimension D: tokens per tile a multiple of 128.
+template <int D>
+hipError_t launch_backward_staged(const bf16_raw *qq, const bf16_raw *kk, const bf16_raw *vv, const void *o, const bf16_raw *gg,
+                                  const float *lse, float *delta, bool compute_delta, void *d_q, void *d_k, void *d_v, int B,
+                                  const FwdParams &p, const WindowTable &win, hipStream_t stream)
 {
-    if (!backward_supported((int)p.P, D)) return hipErrorInvalidValue;
-    const bf16_raw *qq = static_cast<const bf16_raw *>(q), *kk = static_cast<const bf16_raw *>(k);
-    const bf16_raw *vv = static_cast<const bf16_raw *>(v), *gg = static_cast<const bf16_raw *>(d_o);
-    if (D == 64)
-        return launch_backward_generic<64>(qq, kk, vv, o, d_o, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream);
-    if (p.P % kCols != 0)
-        return launch_backward_generic<128>(qq, kk, vv, o, d_o, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream);
     // the workspace holds two floats per row here: -delta, then -lse / scale
     const size_t rows = (size_t)B * p.H * p.N;       // all heads of the tensor at once
     float *neg_delta = delta, *neg_lse = delta + rows;
     if (compute_delta) {
-        sta_bwd_delta_kernel<<<dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, stream>>>(
-            static_cast<const uint4 *>(o), static_cast<const uint4 *>(d_o), lse, kLog2e / p.scale_log2e, neg_delta, neg_lse,
-            rows);
+        constexpr unsigned per_block = 256 / (D / 8);
+        sta_bwd_delta_kernel<D><<<dim3((unsigned)((rows + per_block - 1) / per_block)), dim3(256), 0, stream>>>(
+            static_cast<const uint4 *>(o), reinterpret_cast<const uint4 *>(gg), lse, kLog2e / p.scale_log2e, neg_delta,
+            neg_lse, rows);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -906,21 +959,37 @@ hipError_t launch_backward(const void *q, const void *k, const void *v, const vo
     // 18.5, 18.5, 19.3 ms.
     const uint32_t chunk = p.n_w * (p.P / kCols);
     dim3 block(kNW * 64);
-    sta_bwd_dq_kernel<<<grid_for(chunk), block, 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_q), p, win, n_bh, chunk);
+    sta_bwd_dq_kernel<D><<<grid_for(chunk), block, 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_q), p,
+                                                               win, n_bh, chunk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.P % 192 == 0) {
         // 192 keys per workgroup: the chunk is again one row of tiles along w
         const uint32_t total6 = (p.N / 192) * n_bh, chunk6 = p.n_w * (p.P / 192);
         const dim3 grid6(8 * chunk6 * ((((total6 + chunk6 - 1) / chunk6) + 7) / 8));
-        sta_bwd_dkv_kernel<6><<<grid6, dim3(768), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_k),
-                                                                  static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk6);
+        sta_bwd_dkv_kernel<D, 6><<<grid6, dim3(768), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_k),
+                                                                 static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk6);
     } else {
-        sta_bwd_dkv_kernel<4><<<grid_for(chunk), dim3(512), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta,
-                                                                            static_cast<bf16_raw *>(d_k),
-                                                                            static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk);
+        sta_bwd_dkv_kernel<D, 4><<<grid_for(chunk), dim3(512), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta,
+                                                                           static_cast<bf16_raw *>(d_k),
+                                                                           static_cast<bf16_raw *>(d_v), p, win, n_bh, chunk);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_backward(const void *q, const void *k, const void *v, const void *o, const void *d_o, const float *lse,
+                           float *delta, bool compute_delta, void *d_q, void *d_k, void *d_v, int B, int D,
+                           const FwdParams &p, const WindowTable &win, hipStream_t stream)
+{
+    if (!backward_supported((int)p.P, D)) return hipErrorInvalidValue;
+    const bf16_raw *qq = static_cast<const bf16_raw *>(q), *kk = static_cast<const bf16_raw *>(k);
+    const bf16_raw *vv = static_cast<const bf16_raw *>(v), *gg = static_cast<const bf16_raw *>(d_o);
+    const bool staged = p.P % kCols == 0;
+    if (D == 64)
+        return staged ? launch_backward_staged<64>(qq, kk, vv, o, gg, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream)
+                      : launch_backward_generic<64>(qq, kk, vv, o, d_o, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream);
+    return staged ? launch_backward_staged<128>(qq, kk, vv, o, gg, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream)
+                  : launch_backward_generic<128>(qq, kk, vv, o, d_o, lse, delta, compute_delta, d_q, d_k, d_v, B, p, win, stream);
 }
 
 }  // namespace sta

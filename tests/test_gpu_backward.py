@@ -91,15 +91,17 @@ def test_backward_parity_whole(name, B, H, grid, tile, windows, scale):
 
 
 @pytest.mark.parametrize("name,D,grid,tile,windows", [
-    # head dimension 64 with the paper's 384-token tile, and with a 64-token 2D tile
+    # head dimension 64 with the paper's 384-token tile and with a 128-token tile (the staged kernels, six and four
+    # pairs of waves in the dK/dV kernel), and with a 64-token 2D tile (the general kernels)
     ("bwd-d64-p384", 64, (6, 16, 24), (6, 8, 8), [(1, 3, 3), (1, 1, 2)]),
+    ("bwd-d64-p128", 64, (4, 16, 24), (2, 8, 8), [(3, 1, 3), (1, 3, 1)]),
     ("bwd-d64-p64-2d", 64, (1, 32, 40), (1, 8, 8), [(1, 3, 3), (1, 5, 1)]),
     # head dimension 128 with tiles that are not multiples of 128 tokens
     ("bwd-d128-p64", 128, (2, 8, 24), (1, 8, 8), [(3, 1, 3), (1, 1, 1)]),
     ("bwd-d128-p96", 128, (4, 12, 16), (2, 6, 8), [(1, 3, 1), (3, 3, 3)]),
 ])
 def test_backward_parity_general_shapes(name, D, grid, tile, windows):
-    """Head dimension 64 and tiles of 32*k tokens go through the general kernels."""
+    """Head dimension 64 on both sets of kernels, and tiles of 32*k tokens, which go through the general kernels."""
     w = syn.custom(name, 1, len(windows), D, grid, tile, windows, "bf16", seed=1210)
     q, k, v = syn.make_qkv(w)
     g = syn.make_dout(w)
@@ -131,7 +133,8 @@ def test_backward_kept_set_read_from_dv():
     0: the transposed key-tile set, read exactly (every value is a small integer multiple of a power of two only when
     the kept count is; so the test compares against the oracle's box with a tolerance far below one token)."""
     for D, grid, tile, window in ((128, (4, 16, 16), (2, 8, 8), (3, 1, 3)), (64, (1, 24, 40), (1, 8, 8), (1, 3, 5)),
-                                  (128, (6, 16, 24), (6, 8, 8), (1, 3, 2))):
+                                  (128, (6, 16, 24), (6, 8, 8), (1, 3, 2)), (64, (6, 16, 24), (6, 8, 8), (1, 3, 2)),
+                                  (64, (4, 16, 16), (2, 8, 8), (3, 1, 3))):
         w = syn.custom("bwd-kept", 1, 1, D, grid, tile, [window], "bf16", seed=1)
         assert w.n_tiles <= D
         counts, lists = orc.key_tiles(w.grid, w.tile, orc.window_tiles_to_tokens(window, w.tile))
