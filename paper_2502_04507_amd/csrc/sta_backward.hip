@@ -463,11 +463,12 @@ __global__ __launch_bounds__(kNW * 64, 2) void sta_bwd_dq_kernel(const bf16_raw 
 // from the first to the second through 2 KB of LDS.  Four matrix products per block, no duplicate work inside the
 // kernel, and each wave keeps one accumulator set: at head dimension 128, per wave and 32-query sub-block 32 matrix
 // instructions, 40 vector instructions and 26 LDS reads in 158 registers, so that three waves per SIMD fit (six pairs:
-// 192 keys per workgroup).  LDS stage: Q and dO (each read by rows and transposed) and the row statistics of the 32 queries.
+// 192 keys per workgroup); at head dimension 64 it is 106 registers and two workgroups of four pairs share a CU.
+// LDS stage: Q and dO (each read by rows and transposed) and the row statistics of the 32 queries.
 // A lane holds key column c16 of its wave's two 16-key blocks and the query rows 4*g4 .. 4*g4+3 of a result.
 // ---------------------------------------------------------------------------------------------------------
 template <int D, int NPAIR>
-__global__ __launch_bounds__(NPAIR * 128, 1) void sta_bwd_dkv_kernel(const bf16_raw *__restrict__ q,
+__global__ __launch_bounds__(NPAIR * 128, (D == 64 && NPAIR == 4) ? 2 : 1) void sta_bwd_dkv_kernel(const bf16_raw *__restrict__ q,
                                                                      const bf16_raw *__restrict__ k,
                                                                      const bf16_raw *__restrict__ v,
                                                                      const bf16_raw *__restrict__ d_o,
@@ -963,8 +964,11 @@ hipError_t launch_backward_staged(const bf16_raw *qq, const bf16_raw *kk, const 
                                                                win, n_bh, chunk);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (p.P % 192 == 0) {
-        // 192 keys per workgroup: the chunk is again one row of tiles along w
+    // Head dimension 128: six pairs (192 keys per workgroup, three waves per SIMD) where the tile allows.  Head
+    // dimension 64 needs 106 registers, so two workgroups of four pairs share a CU (four waves per SIMD); measured on
+    // the 30x48x80 grid with 384-token tiles: 21.7 ms for the entry point against 24.9-25.1 ms with six pairs.
+    if (D == 128 && p.P % 192 == 0) {
+        // the chunk is again one row of tiles along w
         const uint32_t total6 = (p.N / 192) * n_bh, chunk6 = p.n_w * (p.P / 192);
         const dim3 grid6(8 * chunk6 * ((((total6 + chunk6 - 1) / chunk6) + 7) / 8));
         sta_bwd_dkv_kernel<D, 6><<<grid6, dim3(768), 0, stream>>>(qq, kk, vv, gg, neg_lse, neg_delta, static_cast<bf16_raw *>(d_k),
