@@ -209,11 +209,12 @@ def test_attention_scores_outgrow_the_first_offset(tile, grid, D, windows):
     ramp[order] = ramp_tiled
     k = (k.float() * ramp[None, None, :, None]).to(torch.bfloat16)
     q = (q.float() * 2.0).to(torch.bfloat16)
-    out = gu.gpu_chain(w, q, k, v).float().numpy()
-    assert np.isfinite(out).all()
-    for h in range(2):
-        ref = gu.oracle_rows(w, q, k, v, 0, h, None)
-        gu.assert_parity(out[0, h], ref, "outgrow h%d" % h)
+    refs = [gu.oracle_rows(w, q, k, v, 0, h, None) for h in range(2)]
+    for workspace in (False, True):       # whole items, and (head dimension 128) items cut into parts along the keys
+        out = gu.gpu_chain(w, q, k, v, workspace=workspace).float().numpy()
+        assert np.isfinite(out).all()
+        for h in range(2):
+            gu.assert_parity(out[0, h], refs[h], "outgrow h%d workspace=%s" % (h, workspace))
 
 
 def test_attention_large_scores_stay_finite():
