@@ -735,8 +735,10 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_
     // The first sub-block of an item sets the exponent offset (the row maxima of its keys).  The rest runs without
     // following the maximum: probabilities, row sums and accumulators have 8 exponent bits, so an offset that
     // turns out too low costs no precision until the sums near the end of that range.  The row sums are looked at
-    // once at the end; if one is beyond 2^64 or not a number, the workgroup does the whole item again with the
+    // once at the end; if one is beyond 2^96 or not a number, the workgroup does the whole item again with the
     // careful loop, which moves the offset whenever a score exceeds it by more than 2^8 in the exponent.
+    // (2^96 leaves 66 in the exponent of e between the first keys' maximum and the largest score before the second
+    // pass is needed, and room for |V| up to 2^32 in the accumulators; those are checked as well.)
     sub_block(std::true_type{}, std::integral_constant<int, 0>{}, 0);
     for (int iter = 1; iter < n_iter; iter += STAGES) {
         static_for<0, STAGES>([&](auto st) {
@@ -746,9 +748,17 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_fast_kernel(const bf16_
         });
     }
     float l_tot = half_swap_sum(l_run);
-    constexpr float kRedoAbove = 18446744073709551616.f;      // 2^64
-    // (the comparison is false for a NaN; the barrier inside also ends every wave's reads of the stages)
-    if (__builtin_expect(__syncthreads_or(!(l_tot < kRedoAbove)), 0)) {
+    constexpr float kRedoAbove = 79228162514264337593543950336.f;      // 2^96
+    // The accumulators too: with |V| beyond 2^32 they can leave the range before the row sums reach the bound.  The
+    // test is on the bit patterns (largest exponent field), so that it sees a NaN (infinity minus infinity) as well.
+    uint32_t o_max = 0;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_max = max(o_max, __float_as_uint(Oacc[db][r]) & 0x7fffffffu);
+    // (With finite inputs a row sum is never a NaN: a probability that overflows is +infinity, and so is the sum.
+    // The barrier inside also ends every wave's reads of the stages.)
+    if (__builtin_expect(__syncthreads_or(!(l_tot < kRedoAbove) || o_max >= 0x7f800000u), 0)) {
         m_run = -INFINITY;
         l_run = 0.f;
 #pragma unroll
@@ -1231,8 +1241,10 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
     // whose relative precision does not depend on their size, so an offset that turns out too low costs nothing
     // until the sums near the end of that range.  The remaining sub-blocks therefore run WITHOUT following the
     // maximum (ten vector instructions and a branch less per sub-block), and the row sums are looked at once at the
-    // end: if one of them is beyond 2^64 or not a number, the workgroup does the whole item again with the careful
-    // loop, which re-bases whenever a score exceeds the offset by more than 2^8 in the exponent.
+    // end: if one of them is beyond 2^96 or not a number, or an accumulator has left the range, the workgroup does the
+    // whole item again with the careful loop, which re-bases whenever a score exceeds the offset by more than 2^8 in
+    // the exponent.  (2^96 leaves 66 in the exponent of e between the first keys' maximum and the largest score before
+    // the second pass is needed, and room for |V| up to 2^32 in the accumulators.)
     next_sub_block();
     sub_block_at(std::true_type{}, 0u, __uint_as_float(0xff800000u));
 #pragma unroll 1
@@ -1243,9 +1255,19 @@ __global__ __launch_bounds__(NW * 64, MINB) void sta_fwd_x32_kernel(const bf16_r
     float l_tot[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) l_tot[qb] = quad_lane_sum(l_run[qb]);
-    constexpr float kRedoAbove = 18446744073709551616.f;      // 2^64
-    // (the comparison is false for a NaN; the barrier inside also ends every wave's reads of the stages)
-    if (__builtin_expect(__syncthreads_or(!(l_tot[0] < kRedoAbove && l_tot[1] < kRedoAbove)), 0)) {
+    constexpr float kRedoAbove = 79228162514264337593543950336.f;      // 2^96
+    // The accumulators too: with |V| beyond 2^32 they can leave the range before the row sums reach the bound.  The
+    // test is on the bit patterns (largest exponent field), so that it sees a NaN (infinity minus infinity) as well.
+    uint32_t o_max = 0;
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o_max = max(o_max, __float_as_uint(Oacc[cb][qb][r]) & 0x7fffffffu);
+    // (With finite inputs a row sum is never a NaN: a probability that overflows is +infinity, and so is the sum.
+    // The barrier inside also ends every wave's reads of the stages.)
+    if (__builtin_expect(__syncthreads_or(!(l_tot[0] < kRedoAbove && l_tot[1] < kRedoAbove) || o_max >= 0x7f800000u), 0)) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             m_run[qb] = 0.f;

@@ -217,6 +217,29 @@ def test_attention_scores_outgrow_the_first_offset(tile, grid, D, windows):
             gu.assert_parity(out[0, h], refs[h], "outgrow h%d workspace=%s" % (h, workspace))
 
 
+@pytest.mark.parametrize("tile,grid,D", [((6, 8, 8), (6, 16, 24), 128), ((2, 8, 8), (4, 16, 16), 128), ((6, 8, 8), (6, 16, 24), 64)])
+def test_attention_accumulators_outgrow_fp32_before_the_row_sums_do(tile, grid, D):
+    """All queries are the all-ones vector; the keys of one tile are 4.875 * ones, all others zero, so that tile's
+    scores exceed every other by 55 (2^79 as a factor): row sums stay below the bound at which the kernel repeats
+    an item carefully, but with V scaled by 2^50 the unnormalised accumulators pass 2^128.  The kernel has to
+    notice that as well.  Attention is linear in V and the scaling is by a power of two, so the result must be
+    2^50 times the oracle's result for the unscaled V."""
+    w = syn.custom("vhuge", 1, 2, D, grid, tile, [(3, 3, 3), (1, 3, 3)], "bf16", seed=85)
+    _, _, v = syn.make_qkv(w)
+    order = torch.from_numpy(orc.tile_order(w.grid, w.tile))
+    q = torch.ones((1, 2, w.N, D), dtype=torch.bfloat16)
+    k = torch.zeros((1, 2, w.N, D), dtype=torch.bfloat16)
+    hot_tile = w.n_tiles - 1                                       # last tile in tiled order
+    k[:, :, order[hot_tile * w.P:(hot_tile + 1) * w.P], :] = 4.875 * (128.0 / D) ** 0.5     # same score at both head dimensions
+    big = (v.float() * 2.0 ** 50).to(torch.bfloat16)
+    for workspace in (False, True):
+        out = gu.gpu_chain(w, q, k, big, workspace=workspace).float().numpy() * 2.0 ** -50
+        assert np.isfinite(out).all()
+        for h in range(2):
+            ref = gu.oracle_rows(w, q, k, v, 0, h, None)
+            gu.assert_parity(out[0, h], ref, "vhuge h%d workspace=%s" % (h, workspace))
+
+
 def test_attention_large_scores_stay_finite():
     """Scores of a few hundred before scaling: exponent offsets must keep everything finite."""
     w = syn.custom("bigscores", 1, 1, 128, (6, 8, 16), (6, 8, 8), [(1, 1, 3)], "bf16", seed=80)
