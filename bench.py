@@ -473,6 +473,15 @@ def main():
                       "sta_tile_permute_ms": pt["median"],
                       "sta_tile_permute_GBs": 2.0 * nbytes / (pt["median"] * 1e-3) / 1e9,
                       "sta_tile_permute_frac_of_plain_copy": ct["median"] / pt["median"]})
+            if not args.no_backward and wl.P % 128 == 0 and other.q.dtype == torch.bfloat16:
+                # the gradient entry point on the same resident tensors (dO: the raster Q; outputs over raster K, V, O)
+                lse_o = torch.empty((wl.B, wl.H, wl.N), dtype=torch.float32, device=device)
+                sta.sta_forward_lse(other.qt, other.kt, other.vt, other.ot, lse_o, wl.grid, wl.tile, wl.window_tiles)
+                bws_o = torch.empty(sta.sta_backward_workspace_bytes(wl.B, wl.H, wl.grid), dtype=torch.uint8, device=device)
+                b_ms = event_time_ms(lambda: sta.sta_backward(other.qt, other.kt, other.vt, other.ot, other.q, lse_o, other.k,
+                                                              other.v, other.o, wl.grid, wl.tile, wl.window_tiles, bws_o), 5)
+                f.update({"sta_backward_ms": b_ms, "sta_backward_tflops_executed": 3.5 * fl / (b_ms * 1e-3) / 1e12})
+                del lse_o, bws_o
             configs[name] = f
             del other
         out["configs"] = configs
