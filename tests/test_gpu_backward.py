@@ -183,10 +183,12 @@ def test_backward_is_bit_reproducible():
             assert torch.equal(a.view(torch.int16), bb.view(torch.int16))
 
 
-def test_backward_full_size_sampled():
-    """Headline shape (115,200 tokens, window 3x3x3), one head checked: dQ on sampled query rows, dK/dV on sampled
-    key rows of a corner tile and an interior tile (each summed by the oracle over every query that keeps them)."""
-    w = syn.workload("C4")
+@pytest.mark.parametrize("config", ["C4", "D64-3D"])
+def test_backward_full_size_sampled(config):
+    """Headline shape (115,200 tokens, window 3x3x3) at head dimension 128 and 64, one head checked: dQ on sampled
+    query rows, dK/dV on sampled key rows of a corner tile and an interior tile (each summed by the oracle over every
+    query that keeps them)."""
+    w = syn.workload(config)
     q, k, v = syn.make_qkv(w)
     g = syn.make_dout(w)
     (dq, dk, dv), _ = gpu_backward(w, q, k, v, g)
@@ -198,9 +200,9 @@ def test_backward_full_size_sampled():
         qidx = gu.stratified_query_sample(w, 40, [], seed=400 + h)
         kidx = np.unique(np.concatenate([order[t * w.P + rng.integers(0, w.P, size=3)] for t in tiles])).astype(np.int64)
         rq, rk, rv = oracle_backward(w, q, k, v, g, 0, h, query_idx=qidx, key_idx=kidx)
-        assert_grad_parity(dq[0, h][qidx].float().numpy(), rq, "C4 dQ h%d" % h)
-        assert_grad_parity(dk[0, h][kidx].float().numpy(), rk, "C4 dK h%d" % h)
-        assert_grad_parity(dv[0, h][kidx].float().numpy(), rv, "C4 dV h%d" % h)
+        assert_grad_parity(dq[0, h][qidx].float().numpy(), rq, "%s dQ h%d" % (config, h))
+        assert_grad_parity(dk[0, h][kidx].float().numpy(), rk, "%s dK h%d" % (config, h))
+        assert_grad_parity(dv[0, h][kidx].float().numpy(), rv, "%s dV h%d" % (config, h))
 
 
 def test_backward_errors():
