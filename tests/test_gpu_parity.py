@@ -434,6 +434,11 @@ def test_attention_parity_c5_mixed_windows_sampled():
     _sampled_full_size("C5", n_random=8, heads_with_full_tile=set(), rows_per_stratum=8)
 
 
+def test_attention_parity_head_dimension_64_full_size_sampled():
+    """The headline grid, tile and window at head dimension 64 (the 12-wave instance of the other attention kernel)."""
+    _sampled_full_size("D64-3D", n_random=8, heads_with_full_tile=set(), heads=[0, 9, 17, 23], rows_per_stratum=8)
+
+
 def test_attention_parity_c4_dense_sampled():
     _sampled_full_size("C4dense", n_random=16, heads_with_full_tile=set(), heads=[0, 7, 23], rows_per_stratum=16)
 
